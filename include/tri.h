@@ -1,0 +1,163 @@
+/*
+ * tri.h -- C ABI of the MI355X (gfx950) TriAttention KV-cache compression step.
+ *
+ * The step, per (sequence, layer, KV head) -- a "head-instance" -- over its N cached
+ * pre-RoPE keys:
+ *   1. score    S~(g)(k): trigonometric-series score + concentration-weighted norm score,
+ *               averaged over the future offsets D, for each of the G query heads that share
+ *               the KV head                                   (Sections 4.1, 4.2)
+ *   2. reduce   z-score every head's scores over the N keys, take the maximum over the
+ *               G heads -> S_final(k)                         (Section 4.3, GQA)
+ *   3. select   the B keys with the largest S_final           (Section 4.3)
+ *   4. compact  move the survivors' K, V and positions to the front of the cache
+ *               ("evict the rest", Section 4.3)
+ *
+ * Conventions for every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller, except tri_model itself, the
+ *     tri_cache structs themselves and tri_model::offsets, which are HOST memory read during
+ *     the call only.  The library allocates nothing and keeps no pointer after a call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on that stream; they never synchronise.  Arguments are validated on the
+ *     host before anything is enqueued; on error nothing is enqueued.
+ *   - Return value: TRI_OK or a negative tri_status.  Nothing aborts or throws.
+ *     tri_last_error() returns a static string describing the last failure on the calling thread.
+ *   - Non-finite key or statistics values: behaviour undefined.
+ *   - head_dim must be 128 (64 frequency bands); n_q_heads / n_kv_heads (= G) must be 1, 2, 4 or 8;
+ *     positions, cur_pos and cur_pos + max(offsets) must be below 2^62 in magnitude (positions
+ *     and cur_pos are int32).
+ */
+#ifndef TRI_H
+#define TRI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TRI_OK = 0,
+    TRI_ERR_INVALID_ARG = -1, /* a NULL pointer, a size or stride out of range        */
+    TRI_ERR_UNSUPPORTED = -2, /* a head_dim / group size / layout this build lacks   */
+    TRI_ERR_WORKSPACE = -3,   /* workspace NULL, misaligned (256 B) or too small      */
+    TRI_ERR_HIP = -4          /* a HIP launch reported an error                       */
+} tri_status;
+
+typedef enum { TRI_F32 = 0, TRI_BF16 = 1 } tri_dtype;
+
+/* which two elements of a head vector form frequency band f */
+typedef enum {
+    TRI_PAIR_INTERLEAVED = 0, /* (x[2f], x[2f+1]) -- Section 2.1 Eq. 1                  */
+    TRI_PAIR_HALF = 1         /* (x[f], x[f + head_dim/2]) -- half-split checkpoints  */
+} tri_pair_layout;
+
+/* Model geometry and the scoring hyper-parameters (Section 2.1: omega_f = theta^(-2f/d);
+ * Section 4.2: the offset set D, geometric in the paper). */
+typedef struct tri_model {
+    int32_t n_layers;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    double rope_theta;
+    int32_t pairs;          /* tri_pair_layout */
+    int32_t n_offsets;      /* |D| >= 1 */
+    const int64_t *offsets; /* HOST array [n_offsets] */
+} tri_model;
+
+/*
+ * A KV cache holding pre-RoPE keys, values and key positions for n_layers x n_seqs x n_kv_heads
+ * head-instances.  One descriptor covers both layouts:
+ *   contiguous (block_size == 0): slot n of (layer l, sequence s, head h) is at element
+ *       l*stride_layer + s*stride_seq_or_block + h*stride_head + n*stride_slot
+ *   paged (block_size > 0, a power of two): with b = block_table[s*max_blocks_per_seq + n/block_size],
+ *       l*stride_layer + b*stride_seq_or_block + h*stride_head + (n % block_size)*stride_slot
+ * of k and of v (elements of `dtype`; a slot's head_dim elements are contiguous and 16-byte
+ * aligned).  Positions use the same formula with the pos_* strides and a slot stride of 1;
+ * they are stored per head because heads keep different tokens once compacted.
+ */
+typedef struct tri_cache {
+    void *k;
+    void *v; /* may be NULL for tri_score / tri_select_topk */
+    int32_t *pos;
+    int32_t dtype;                /* tri_dtype */
+    int32_t n_seqs;               /* S */
+    const int32_t *seq_len;       /* device [S]: N_s, number of occupied slots          */
+    const int32_t *cur_pos;       /* device [S]: p_q, position of the current query      */
+    int32_t max_seq_len;          /* host upper bound on every N_s (sizes grids and the N stride of score arrays) */
+    int32_t block_size;           /* 0 = contiguous */
+    const int32_t *block_table;   /* device [S][max_blocks_per_seq], paged only           */
+    int32_t max_blocks_per_seq;
+    int64_t stride_layer, stride_seq_or_block, stride_head, stride_slot;
+    int64_t pos_stride_layer, pos_stride_seq_or_block, pos_stride_head;
+} tri_cache;
+
+const char *tri_last_error(void);
+
+/*
+ * Offline calibration (Section 4.1 text under both score equations; Appendix B.5): per
+ * (layer, query head, band f) the complex mean of the pre-RoPE query samples, E[q_f], and the
+ * mean modulus E||q_f||.
+ *   q_samples    device [n_tokens][n_layers][n_q_heads][head_dim], q_dtype
+ *   centers_out  device [n_layers][n_q_heads][head_dim/2][3] float = (Re E[q_f], Im E[q_f], E||q_f||)
+ * Sums are accumulated in double in a fixed order (deterministic).  n_tokens >= 1.
+ */
+tri_status tri_build_centers(const tri_model *model, const void *q_samples, int32_t q_dtype,
+                             int64_t n_tokens, float *centers_out, void *stream);
+
+/* Bytes of scratch tri_score / tri_select_topk / tri_compress_step need for this model, cache
+ * geometry and budget (the maximum over the three).  0 on invalid arguments. */
+size_t tri_workspace_size(const tri_model *model, const tri_cache *cache, int32_t budget);
+
+/*
+ * Steps 1-2: scores of every cached key (Sections 4.1-4.3).
+ *   centers    device [n_layers][n_q_heads][F][3], as written by tri_build_centers
+ *   final_out  device [n_layers][n_seqs][n_kv_heads][max_seq_len] float: S_final; entries at
+ *              n >= N_s are not written
+ *   raw_out    NULL, or device [n_layers][n_seqs][n_q_heads][max_seq_len] float: S~(g), query
+ *              head h*G+g belonging to KV head h
+ *   workspace  device, 256-byte aligned, ws_bytes >= tri_workspace_size(); contents undefined after
+ * sigma is the population standard deviation; a head with sigma = 0 contributes 0 to the maximum.
+ */
+tri_status tri_score(const tri_model *model, const float *centers, const tri_cache *cache,
+                     float *final_out, float *raw_out, void *workspace, size_t ws_bytes,
+                     void *stream);
+
+/*
+ * Step 3: per head-instance the min(N_s, budget) keys with the largest final score, equal
+ * scores resolved in favour of the lower slot index (-0.0 equals +0.0).
+ *   final_scores  device [n_layers][n_seqs][n_kv_heads][max_seq_len] float
+ *   kept_idx      device [n_layers][n_seqs][n_kv_heads][budget] int32: kept slots, ascending;
+ *                 entries past the count are not written
+ *   kept_cnt      device [n_layers][n_seqs][n_kv_heads] int32 = min(N_s, budget)
+ */
+tri_status tri_select_topk(const tri_model *model, const float *final_scores,
+                           const tri_cache *cache, int32_t budget, int32_t *kept_idx,
+                           int32_t *kept_cnt, void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Step 4: slot j of dst <- slot kept_idx[j] of src, for K, V and positions, j < kept_cnt.
+ * dst may describe the same memory as src (in-place compaction; also for the paged layout,
+ * where the survivors fill the sequence's first blocks and the caller frees the rest).  If
+ * dst is a different cache it must not overlap src.  dst uses its own strides / block table
+ * and src's n_seqs and dtype; dst->seq_len, cur_pos and max_seq_len are ignored.
+ *   new_seq_len  NULL or device [n_seqs] int32 <- min(N_s, budget)
+ */
+tri_status tri_compact(const tri_model *model, const tri_cache *src, const tri_cache *dst,
+                       int32_t budget, const int32_t *kept_idx, const int32_t *kept_cnt,
+                       int32_t *new_seq_len, void *stream);
+
+/*
+ * Steps 1-4 in one call, pipelined over layers so that the per-layer score arrays stay in
+ * cache between the kernels.  Same arguments and results as the three calls above; raw and
+ * final scores live in the workspace only.
+ */
+tri_status tri_compress_step(const tri_model *model, const float *centers, const tri_cache *src,
+                             const tri_cache *dst, int32_t budget, int32_t *kept_idx,
+                             int32_t *kept_cnt, int32_t *new_seq_len, void *workspace,
+                             size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TRI_H */

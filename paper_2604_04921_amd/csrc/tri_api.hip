@@ -1,0 +1,280 @@
+// C-ABI entry points: host-side validation and dispatch.  See include/tri.h for the contract.
+#include <cstdarg>
+#include <cstdio>
+
+#include "tri_internal.h"
+
+namespace tri {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof g_error, fmt, ap);
+    va_end(ap);
+}
+
+tri_status hip_status(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return TRI_OK;
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return TRI_ERR_HIP;
+}
+
+tri_status check_model(const tri_model *m)
+{
+    if (!m) {
+        set_error("model is NULL");
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (m->n_layers < 1 || m->n_q_heads < 1 || m->n_kv_heads < 1 || m->n_q_heads % m->n_kv_heads != 0) {
+        set_error("bad geometry: layers %d, q heads %d, kv heads %d", m->n_layers, m->n_q_heads, m->n_kv_heads);
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (m->head_dim != kHeadDim) {
+        set_error("head_dim %d not built (128 only)", m->head_dim);
+        return TRI_ERR_UNSUPPORTED;
+    }
+    const int G = m->n_q_heads / m->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) {
+        set_error("group size %d not built (1, 2, 4, 8)", G);
+        return TRI_ERR_UNSUPPORTED;
+    }
+    if (!(m->rope_theta > 1.0)) {
+        set_error("rope_theta must be > 1");
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (m->pairs != TRI_PAIR_INTERLEAVED && m->pairs != TRI_PAIR_HALF) {
+        set_error("unknown pair layout %d", m->pairs);
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (m->n_offsets < 1 || m->n_offsets > kMaxOffsets || !m->offsets) {
+        set_error("n_offsets must be in [1, %d] with a host offsets array", kMaxOffsets);
+        return TRI_ERR_INVALID_ARG;
+    }
+    for (int j = 0; j < m->n_offsets; ++j)
+        if (m->offsets[j] > ((int64_t)1 << 61) || m->offsets[j] < -((int64_t)1 << 61)) {
+            set_error("offset %d out of range", j);
+            return TRI_ERR_INVALID_ARG;
+        }
+    return TRI_OK;
+}
+
+static bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+tri_status check_cache(const tri_model *m, const tri_cache *c, bool need_v, const char *what)
+{
+    (void)m;
+    if (!c) {
+        set_error("%s cache is NULL", what);
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (!c->k || !c->pos || (need_v && !c->v)) {
+        set_error("%s cache: k, pos%s must not be NULL", what, need_v ? ", v" : "");
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (c->dtype != TRI_F32 && c->dtype != TRI_BF16) {
+        set_error("%s cache: unknown dtype %d", what, c->dtype);
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (c->n_seqs < 1 || c->max_seq_len < 0 || !c->seq_len || !c->cur_pos) {
+        set_error("%s cache: n_seqs >= 1, max_seq_len >= 0, seq_len and cur_pos required", what);
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (c->block_size != 0 && (!pow2(c->block_size) || !c->block_table || c->max_blocks_per_seq < 1 ||
+                               (int64_t)c->max_blocks_per_seq * c->block_size < c->max_seq_len)) {
+        set_error("%s cache: paged layout needs a power-of-two block_size, a block table and "
+                  "max_blocks_per_seq * block_size >= max_seq_len", what);
+        return TRI_ERR_INVALID_ARG;
+    }
+    const int eb = c->dtype == TRI_BF16 ? 2 : 4;
+    const int64_t a16 = 16 / eb;
+    if (c->stride_slot < kHeadDim || c->stride_slot % a16 || c->stride_head % a16 || c->stride_layer % a16 ||
+        c->stride_seq_or_block % a16 || ((uintptr_t)c->k & 15) || ((uintptr_t)c->v & 15)) {
+        set_error("%s cache: slots must be 16-byte aligned and at least head_dim elements apart", what);
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (c->stride_head < 0 || c->stride_layer < 0 || c->stride_seq_or_block < 0 || c->pos_stride_head < 0 ||
+        c->pos_stride_layer < 0 || c->pos_stride_seq_or_block < 0) {
+        set_error("%s cache: negative stride", what);
+        return TRI_ERR_INVALID_ARG;
+    }
+    return TRI_OK;
+}
+
+CacheView make_view(const tri_model &m, const tri_cache &c)
+{
+    CacheView v{};
+    v.k = c.k;
+    v.v = c.v;
+    v.pos = c.pos;
+    v.seq_len = c.seq_len;
+    v.cur_pos = c.cur_pos;
+    v.block_table = c.block_table;
+    v.stride_layer = c.stride_layer;
+    v.stride_sb = c.stride_seq_or_block;
+    v.stride_head = c.stride_head;
+    v.stride_slot = c.stride_slot;
+    v.pos_stride_layer = c.pos_stride_layer;
+    v.pos_stride_sb = c.pos_stride_seq_or_block;
+    v.pos_stride_head = c.pos_stride_head;
+    v.n_seqs = c.n_seqs;
+    v.n_kv_heads = m.n_kv_heads;
+    v.max_seq_len = c.max_seq_len;
+    v.block_shift = -1;
+    if (c.block_size > 0) {
+        v.block_shift = 0;
+        while ((1 << v.block_shift) < c.block_size) ++v.block_shift;
+    }
+    v.max_blocks = c.max_blocks_per_seq;
+    return v;
+}
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+Workspace workspace_layout(const tri_model &m, const tri_cache &c, int32_t budget)
+{
+    (void)budget;
+    Workspace w{};
+    const size_t G = (size_t)(m.n_q_heads / m.n_kv_heads);
+    const size_t inst = (size_t)m.n_layers * c.n_seqs * m.n_kv_heads;
+    const size_t tiles = ((size_t)c.max_seq_len + kScoreTile - 1) / kScoreTile;
+    size_t o = 0;
+    w.band_rev = o;
+    o = align256(o + kBands * sizeof(double));
+    w.table = o;
+    o = align256(o + inst * kBands * 3 * G * sizeof(float));
+    w.partials = o;
+    o = align256(o + inst * tiles * 2 * G * sizeof(double));
+    w.stats = o;
+    o = align256(o + inst * G * 2 * sizeof(double));
+    w.raw = o;
+    o = align256(o + inst * G * (size_t)c.max_seq_len * sizeof(float));
+    w.final_ = o;
+    o = align256(o + inst * (size_t)c.max_seq_len * sizeof(float));
+    w.total = o;
+    return w;
+}
+
+static tri_status check_workspace(const Workspace &wl, void *ws, size_t ws_bytes)
+{
+    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < wl.total) {
+        set_error("workspace must be 256-byte aligned and hold %zu bytes (got %zu)", wl.total, ws_bytes);
+        return TRI_ERR_WORKSPACE;
+    }
+    return TRI_OK;
+}
+
+}  // namespace tri
+
+using namespace tri;
+
+extern "C" {
+
+const char *tri_last_error(void) { return g_error; }
+
+tri_status tri_build_centers(const tri_model *model, const void *q_samples, int32_t q_dtype, int64_t n_tokens,
+                             float *centers_out, void *stream)
+{
+    tri_status rc = check_model(model);
+    if (rc != TRI_OK) return rc;
+    if (!q_samples || !centers_out || n_tokens < 1 || (q_dtype != TRI_F32 && q_dtype != TRI_BF16)) {
+        set_error("tri_build_centers: q_samples, centers_out, n_tokens >= 1 and a known dtype required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    return launch_centers(*model, q_samples, q_dtype, n_tokens, centers_out, (hipStream_t)stream);
+}
+
+size_t tri_workspace_size(const tri_model *model, const tri_cache *cache, int32_t budget)
+{
+    if (check_model(model) != TRI_OK || !cache || cache->n_seqs < 1 || cache->max_seq_len < 0 || budget < 1)
+        return 0;
+    return workspace_layout(*model, *cache, budget).total;
+}
+
+tri_status tri_score(const tri_model *model, const float *centers, const tri_cache *cache, float *final_out,
+                     float *raw_out, void *workspace, size_t ws_bytes, void *stream)
+{
+    tri_status rc = check_model(model);
+    if (rc != TRI_OK) return rc;
+    if ((rc = check_cache(model, cache, false, "tri_score")) != TRI_OK) return rc;
+    if (!centers || !final_out) {
+        set_error("tri_score: centers and final_out required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    const Workspace wl = workspace_layout(*model, *cache, 1);
+    if ((rc = check_workspace(wl, workspace, ws_bytes)) != TRI_OK) return rc;
+    return launch_score(*model, centers, *cache, final_out, raw_out, (char *)workspace, wl, (hipStream_t)stream);
+}
+
+tri_status tri_select_topk(const tri_model *model, const float *final_scores, const tri_cache *cache,
+                           int32_t budget, int32_t *kept_idx, int32_t *kept_cnt, void *workspace,
+                           size_t ws_bytes, void *stream)
+{
+    (void)workspace;
+    (void)ws_bytes;
+    tri_status rc = check_model(model);
+    if (rc != TRI_OK) return rc;
+    if (!cache || cache->n_seqs < 1 || !cache->seq_len || cache->max_seq_len < 0) {
+        set_error("tri_select_topk: cache with n_seqs, seq_len and max_seq_len required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (!final_scores || !kept_idx || !kept_cnt || budget < 1) {
+        set_error("tri_select_topk: final_scores, kept_idx, kept_cnt and budget >= 1 required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    return launch_select(*model, final_scores, *cache, budget, kept_idx, kept_cnt, (hipStream_t)stream);
+}
+
+tri_status tri_compact(const tri_model *model, const tri_cache *src, const tri_cache *dst, int32_t budget,
+                       const int32_t *kept_idx, const int32_t *kept_cnt, int32_t *new_seq_len, void *stream)
+{
+    tri_status rc = check_model(model);
+    if (rc != TRI_OK) return rc;
+    if ((rc = check_cache(model, src, true, "tri_compact src")) != TRI_OK) return rc;
+    if (!dst || !dst->k || !dst->v || !dst->pos) {
+        set_error("tri_compact: dst with k, v, pos required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    tri_cache d = *dst;  // dst borrows the fields it does not own from src
+    d.n_seqs = src->n_seqs;
+    d.dtype = src->dtype;
+    d.seq_len = src->seq_len;
+    d.cur_pos = src->cur_pos;
+    d.max_seq_len = src->max_seq_len;
+    if ((rc = check_cache(model, &d, true, "tri_compact dst")) != TRI_OK) return rc;
+    if (d.block_size > 0 && (int64_t)d.max_blocks_per_seq * d.block_size < (budget < src->max_seq_len ? budget : src->max_seq_len)) {
+        set_error("tri_compact: dst block table too short for the budget");
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (!kept_idx || !kept_cnt || budget < 1) {
+        set_error("tri_compact: kept_idx, kept_cnt and budget >= 1 required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    return launch_compact(*model, *src, d, budget, kept_idx, kept_cnt, new_seq_len, (hipStream_t)stream);
+}
+
+tri_status tri_compress_step(const tri_model *model, const float *centers, const tri_cache *src,
+                             const tri_cache *dst, int32_t budget, int32_t *kept_idx, int32_t *kept_cnt,
+                             int32_t *new_seq_len, void *workspace, size_t ws_bytes, void *stream)
+{
+    tri_status rc = check_model(model);
+    if (rc != TRI_OK) return rc;
+    if ((rc = check_cache(model, src, true, "tri_compress_step src")) != TRI_OK) return rc;
+    if (!centers || !dst || !kept_idx || !kept_cnt || budget < 1) {
+        set_error("tri_compress_step: centers, dst, kept_idx, kept_cnt and budget >= 1 required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    const Workspace wl = workspace_layout(*model, *src, budget);
+    if ((rc = check_workspace(wl, workspace, ws_bytes)) != TRI_OK) return rc;
+    char *ws = (char *)workspace;
+    float *fin = reinterpret_cast<float *>(ws + wl.final_);
+    if ((rc = launch_score(*model, centers, *src, fin, nullptr, ws, wl, (hipStream_t)stream)) != TRI_OK) return rc;
+    if ((rc = launch_select(*model, fin, *src, budget, kept_idx, kept_cnt, (hipStream_t)stream)) != TRI_OK) return rc;
+    return tri_compact(model, src, dst, budget, kept_idx, kept_cnt, new_seq_len, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,143 @@
+// Eviction as compaction (Section 4.3, "evict the rest"): slot j <- slot kept_idx[j] for K, V
+// and the key positions.  Pure byte moves, 16 bytes per lane.
+#include "tri_internal.h"
+
+namespace tri {
+
+namespace {
+
+struct CompactArgs {
+    CacheView src, dst;
+    const int32_t *kept_idx;  // [inst][B]
+    const int32_t *kept_cnt;  // [inst]
+    int32_t *new_seq_len;     // [S] or NULL
+    int32_t budget;
+    int32_t row16;            // 16-byte chunks per K (or V) row
+    int32_t elem_bytes;
+};
+
+__device__ __forceinline__ void decode_inst(const CacheView &c, int inst, int &l, int &s, int &h)
+{
+    h = inst % c.n_kv_heads;
+    s = (inst / c.n_kv_heads) % c.n_seqs;
+    l = inst / (c.n_kv_heads * c.n_seqs);
+}
+
+__device__ __forceinline__ void write_new_len(const CompactArgs &a, int l, int s, int h, int cnt)
+{
+    if (a.new_seq_len && l == 0 && h == 0 && threadIdx.x == 0) a.new_seq_len[s] = cnt;
+}
+
+constexpr int kRowsPerBlock = 64;
+
+// dst and src are different memory: a plain gather.  grid (ceil(B/64), instances), block 256.
+__global__ __launch_bounds__(256) void gather_kernel(CompactArgs a)
+{
+    const int inst = blockIdx.y;
+    int l, s, h;
+    decode_inst(a.src, inst, l, s, h);
+    const int cnt = a.kept_cnt[inst];
+    if (blockIdx.x == 0) write_new_len(a, l, s, h, cnt);
+    const int rows_per_pass = 256 / a.row16;
+    const int r = threadIdx.x / a.row16, part = threadIdx.x % a.row16;
+    const int32_t *idx = a.kept_idx + (int64_t)inst * a.budget;
+    const char *sk = (const char *)a.src.k, *sv = (const char *)a.src.v;
+    char *dk = (char *)a.dst.k, *dv = (char *)a.dst.v;
+    for (int j0 = blockIdx.x * kRowsPerBlock; j0 < (blockIdx.x + 1) * kRowsPerBlock; j0 += rows_per_pass) {
+        const int j = j0 + r;
+        if (j >= cnt) continue;
+        const int n = idx[j];
+        const int64_t so = kv_offset(a.src, l, s, h, n) * a.elem_bytes + part * 16;
+        const int64_t d_o = kv_offset(a.dst, l, s, h, j) * a.elem_bytes + part * 16;
+        const uint4 kv = *reinterpret_cast<const uint4 *>(sk + so);
+        const uint4 vv = *reinterpret_cast<const uint4 *>(sv + so);
+        *reinterpret_cast<uint4 *>(dk + d_o) = kv;
+        *reinterpret_cast<uint4 *>(dv + d_o) = vv;
+        if (part == 0) const_cast<int32_t *>(a.dst.pos)[pos_offset(a.dst, l, s, h, j)] = a.src.pos[pos_offset(a.src, l, s, h, n)];
+    }
+}
+
+constexpr int kInplaceThreads = 1024;
+constexpr int kInplaceUnroll = 4;
+
+// dst is src: an overlapping move with dst row j <= src row kept_idx[j].  One workgroup walks the
+// survivors of a head-instance in ascending chunks: load a chunk into registers, wait for the data,
+// barrier, store.  A chunk's destinations [j0, j0+R) are never the source of a later chunk (those
+// sources are >= j0+R), and all of its own sources have been read before the barrier.
+// grid (instances), block 1024.
+__global__ __launch_bounds__(kInplaceThreads) void inplace_kernel(CompactArgs a)
+{
+    const int inst = blockIdx.x;
+    int l, s, h;
+    decode_inst(a.src, inst, l, s, h);
+    const int cnt = a.kept_cnt[inst];
+    write_new_len(a, l, s, h, cnt);
+    const int rows_per_pass = kInplaceThreads / a.row16;
+    const int r = threadIdx.x / a.row16, part = threadIdx.x % a.row16;
+    const int32_t *idx = a.kept_idx + (int64_t)inst * a.budget;
+    char *kb = (char *)a.dst.k, *vb = (char *)a.dst.v;
+    int32_t *pb = const_cast<int32_t *>(a.dst.pos);
+    for (int j0 = 0; j0 < cnt; j0 += rows_per_pass * kInplaceUnroll) {
+        uint4 kv[kInplaceUnroll], vv[kInplaceUnroll];
+        int32_t pp[kInplaceUnroll];
+        int src_n[kInplaceUnroll];
+#pragma unroll
+        for (int u = 0; u < kInplaceUnroll; ++u) {
+            const int j = j0 + u * rows_per_pass + r;
+            src_n[u] = j < cnt ? idx[j] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kInplaceUnroll; ++u) {
+            const int j = j0 + u * rows_per_pass + r;
+            if (src_n[u] >= 0 && src_n[u] != j) {
+                const int64_t so = kv_offset(a.src, l, s, h, src_n[u]) * a.elem_bytes + part * 16;
+                kv[u] = *reinterpret_cast<const uint4 *>(kb + so);
+                vv[u] = *reinterpret_cast<const uint4 *>(vb + so);
+                if (part == 0) pp[u] = pb[pos_offset(a.src, l, s, h, src_n[u])];
+            }
+        }
+        // the loads must have returned before any thread of the group may overwrite their sources
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kInplaceUnroll; ++u) {
+            const int j = j0 + u * rows_per_pass + r;
+            if (src_n[u] >= 0 && src_n[u] != j) {
+                const int64_t d_o = kv_offset(a.dst, l, s, h, j) * a.elem_bytes + part * 16;
+                *reinterpret_cast<uint4 *>(kb + d_o) = kv[u];
+                *reinterpret_cast<uint4 *>(vb + d_o) = vv[u];
+                if (part == 0) pb[pos_offset(a.dst, l, s, h, j)] = pp[u];
+            }
+        }
+    }
+}
+
+}  // namespace
+
+tri_status launch_compact(const tri_model &m, const tri_cache &src, const tri_cache &dst, int32_t budget,
+                          const int32_t *kept_idx, const int32_t *kept_cnt, int32_t *new_seq_len,
+                          hipStream_t st)
+{
+    const int n_inst = m.n_layers * src.n_seqs * m.n_kv_heads;
+    if (n_inst <= 0) return TRI_OK;
+    CompactArgs a{};
+    a.src = make_view(m, src);
+    a.dst = make_view(m, dst);
+    a.dst.n_seqs = a.src.n_seqs;
+    a.kept_idx = kept_idx;
+    a.kept_cnt = kept_cnt;
+    a.new_seq_len = new_seq_len;
+    a.budget = budget;
+    a.elem_bytes = src.dtype == TRI_BF16 ? 2 : 4;
+    a.row16 = kHeadDim * a.elem_bytes / 16;
+    const bool same = dst.k == src.k || dst.v == src.v || dst.pos == src.pos;
+    if (same) {
+        hipLaunchKernelGGL(inplace_kernel, dim3(n_inst), dim3(kInplaceThreads), 0, st, a);
+        return hip_status("inplace_kernel");
+    }
+    hipLaunchKernelGGL(gather_kernel, dim3((budget + kRowsPerBlock - 1) / kRowsPerBlock, n_inst), dim3(256), 0,
+                       st, a);
+    return hip_status("gather_kernel");
+}
+
+}  // namespace tri

@@ -1,0 +1,81 @@
+// Internal declarations shared by the HIP translation units of libtri (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "tri.h"
+
+namespace tri {
+
+constexpr int kHeadDim = 128;
+constexpr int kBands = 64;        // F = head_dim / 2
+constexpr int kScoreTile = 256;   // keys scored by one workgroup
+constexpr int kMaxOffsets = 64;
+constexpr int kMaxGroup = 8;
+
+// Device-side view of a tri_cache (plain copy of the descriptor's fields).
+struct CacheView {
+    const void *k;
+    const void *v;
+    const int32_t *pos;
+    const int32_t *seq_len;
+    const int32_t *cur_pos;
+    const int32_t *block_table;
+    int64_t stride_layer, stride_sb, stride_head, stride_slot;
+    int64_t pos_stride_layer, pos_stride_sb, pos_stride_head;
+    int32_t n_seqs, n_kv_heads;
+    int32_t max_seq_len;
+    int32_t block_shift;   // log2(block_size), -1 = contiguous
+    int32_t max_blocks;
+};
+
+// Element offset of slot n of (layer, seq, head) in k / v.
+__device__ __forceinline__ int64_t kv_offset(const CacheView &c, int l, int s, int h, int n)
+{
+    int64_t base = (int64_t)l * c.stride_layer + (int64_t)h * c.stride_head;
+    if (c.block_shift < 0) return base + (int64_t)s * c.stride_sb + (int64_t)n * c.stride_slot;
+    int b = c.block_table[(int64_t)s * c.max_blocks + (n >> c.block_shift)];
+    return base + (int64_t)b * c.stride_sb + (int64_t)(n & ((1 << c.block_shift) - 1)) * c.stride_slot;
+}
+
+// Element offset of slot n of (layer, seq, head) in pos.
+__device__ __forceinline__ int64_t pos_offset(const CacheView &c, int l, int s, int h, int n)
+{
+    int64_t base = (int64_t)l * c.pos_stride_layer + (int64_t)h * c.pos_stride_head;
+    if (c.block_shift < 0) return base + (int64_t)s * c.pos_stride_sb + n;
+    int b = c.block_table[(int64_t)s * c.max_blocks + (n >> c.block_shift)];
+    return base + (int64_t)b * c.pos_stride_sb + (n & ((1 << c.block_shift) - 1));
+}
+
+// Workspace carve-up (all offsets 256-byte aligned).
+struct Workspace {
+    size_t band_rev;   // double [F]: omega_f / 2pi
+    size_t table;      // float  [L][S][Hkv][F][3][G]: folded centre table
+    size_t partials;   // double [L][S][Hkv][n_tiles][2G]: per-tile sum and sum of squares
+    size_t stats;      // double [L][S][Hkv][G][2]: mean and 1/sigma
+    size_t raw;        // float  [L][S][Hq][Nmax] (used when the caller passes no raw_out)
+    size_t final_;     // float  [L][S][Hkv][Nmax] (tri_compress_step only)
+    size_t total;
+};
+Workspace workspace_layout(const tri_model &m, const tri_cache &c, int32_t budget);
+
+void set_error(const char *fmt, ...);
+tri_status check_model(const tri_model *m);
+tri_status check_cache(const tri_model *m, const tri_cache *c, bool need_v, const char *what);
+CacheView make_view(const tri_model &m, const tri_cache &c);
+tri_status hip_status(const char *what);
+
+// launchers (each validates nothing; the entry points in tri_api.hip do)
+tri_status launch_centers(const tri_model &m, const void *q, int32_t q_dtype, int64_t n_tokens,
+                          float *out, hipStream_t st);
+tri_status launch_score(const tri_model &m, const float *centers, const tri_cache &c, float *final_out,
+                        float *raw_out, char *ws, const Workspace &wl, hipStream_t st);
+tri_status launch_select(const tri_model &m, const float *final_scores, const tri_cache &c, int32_t budget,
+                         int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st);
+tri_status launch_compact(const tri_model &m, const tri_cache &src, const tri_cache &dst, int32_t budget,
+                          const int32_t *kept_idx, const int32_t *kept_cnt, int32_t *new_seq_len,
+                          hipStream_t st);
+
+}  // namespace tri

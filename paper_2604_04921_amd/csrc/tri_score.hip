@@ -1,0 +1,400 @@
+// Scoring kernels: table fold, per-key score, moments, z-score + max over the GQA group.
+//
+// Algebra (Sections 4.1-4.2, Appendix B.2).  With q = E[q_f], k = k_f complex, x = p_q + delta - p_k:
+//   ||q|| ||k|| cos(omega x + arg q - arg k) = Re( q conj(k) e^{i omega x} )
+// and the average over the offsets delta in D is linear, so
+//   S~_trig(k) = Re sum_f  Qhat_f * conj( k_f e^{i omega_f p_k} ),
+//   Qhat_f = E[q_f] * (1/|D|) sum_delta e^{i omega_f delta} * e^{i omega_f p_q}.
+// The norm term does not depend on the offset: S_norm(k) = sum_f c_f |k_f|, c_f = E||q_f|| - ||E[q_f]||.
+// The fold kernel builds (Re Qhat, Im Qhat, c) per (layer, sequence, query head, band) in double;
+// the score kernel then needs, per key and band, one rotation of the key by its own position,
+// one modulus, and three FMAs per query head -- independent of |D|.
+#include "tri_internal.h"
+
+namespace tri {
+
+namespace {
+
+constexpr double kTwoPi = 6.283185307179586476925286766559;
+
+struct FoldArgs {
+    const float *centers;   // [L][Hq][F][3]
+    float *table;           // [L][S][Hkv][F][3][G]
+    double *band_rev;       // [F]
+    const int32_t *cur_pos; // [S]
+    int32_t S, Hq, Hkv, G;
+    double theta;
+    int32_t n_off;
+    int64_t offsets[kMaxOffsets];
+};
+
+// exp(2 pi i * frac(t * rev)) in double; t * rev is exact enough for |t| < 2^62 * 2^-53 relative
+__device__ __forceinline__ void unit_phasor(double t, double rev, double *c, double *s)
+{
+    double x = t * rev;
+    x -= floor(x);
+    sincos(kTwoPi * x, s, c);
+}
+
+// grid (Hq, L), block F: thread = band
+__global__ __launch_bounds__(kBands) void fold_kernel(FoldArgs a)
+{
+    const int f = threadIdx.x, qh = blockIdx.x, l = blockIdx.y;
+    // Section 2.1: omega_f = theta^(-2f/d); kept as revolutions per position
+    const double rev = pow(a.theta, -2.0 * (double)f / (double)kHeadDim) / kTwoPi;
+    if (qh == 0 && l == 0) a.band_rev[f] = rev;
+    double er = 0.0, ei = 0.0;
+    for (int j = 0; j < a.n_off; ++j) {
+        double c, s;
+        unit_phasor((double)a.offsets[j], rev, &c, &s);
+        er += c;
+        ei += s;
+    }
+    er /= (double)a.n_off;
+    ei /= (double)a.n_off;
+    const float *ct = a.centers + (((int64_t)l * a.Hq + qh) * kBands + f) * 3;
+    const double qr = (double)ct[0], qi = (double)ct[1], qa = (double)ct[2];
+    const double ar = qr * er - qi * ei, ai = qr * ei + qi * er;
+    const double cn = qa - hypot(qr, qi);
+    const int h = qh / a.G, g = qh % a.G;
+    for (int s = 0; s < a.S; ++s) {
+        double c, sn;
+        unit_phasor((double)a.cur_pos[s], rev, &c, &sn);
+        float *t = a.table + (((((int64_t)l * a.S + s) * a.Hkv + h) * kBands + f) * 3) * a.G;
+        t[0 * a.G + g] = (float)(ar * c - ai * sn);
+        t[1 * a.G + g] = (float)(ar * sn + ai * c);
+        t[2 * a.G + g] = (float)cn;
+    }
+}
+
+struct ScoreArgs {
+    CacheView c;
+    const float *table;
+    const double *band_rev;
+    float *raw;        // [L][S][Hq][Nmax]
+    double *partials;  // [L][S][Hkv][n_tiles][2G]
+    int32_t n_tiles;
+};
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+    static constexpr int kRow16 = 32;  // 16-byte chunks per key row
+};
+template <>
+struct Elem<uint16_t> {
+    static constexpr int kRow16 = 16;
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// One band of one key: rotate the key by its own position, take its modulus, and add the
+// three products per query head.  tb points at this band's [3][G] table entries (wave-uniform).
+template <int G>
+__device__ __forceinline__ void band_update(float (&acc)[G], const float *__restrict__ tb, double pd,
+                                            double rev, float re, float im)
+{
+    double xr = pd * rev;
+    float x = (float)__builtin_amdgcn_fract(xr);   // phase in revolutions, [0, 1]
+    float sn = __builtin_amdgcn_sinf(x);           // v_sin_f32 / v_cos_f32 take revolutions
+    float cs = __builtin_amdgcn_cosf(x);
+    float kr = re * cs - im * sn;
+    float ki = re * sn + im * cs;
+    float m = __builtin_amdgcn_sqrtf(re * re + im * im);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        acc[g] = fmaf(tb[0 * G + g], kr, fmaf(tb[1 * G + g], ki, fmaf(tb[2 * G + g], m, acc[g])));
+}
+
+// grid (n_tiles, S*Hkv, L), block 256: one key per thread, staged through LDS so that global
+// loads are coalesced 16-byte accesses while each thread ends up owning one whole key.
+template <int G, typename T, int PAIRS>
+__global__ __launch_bounds__(kScoreTile) void score_kernel(ScoreArgs a)
+{
+    constexpr int ROW16 = Elem<T>::kRow16;
+    constexpr int STRIDE16 = ROW16 + 1;   // odd number of 16-byte units: conflict-free row reads
+    extern __shared__ uint4 lds[];
+    __shared__ int64_t row_off[kScoreTile];
+    __shared__ double red[4][2 * G];
+
+    const CacheView &c = a.c;
+    const int tid = threadIdx.x;
+    const int tile = blockIdx.x;
+    const int s = blockIdx.y / c.n_kv_heads, h = blockIdx.y % c.n_kv_heads;
+    const int l = blockIdx.z;
+    const int N = c.seq_len[s];
+    const int n0 = tile * kScoreTile;
+    if (n0 >= N) return;
+    const int n = n0 + tid;
+    const bool valid = n < N;
+
+    row_off[tid] = valid ? kv_offset(c, l, s, h, n) : (int64_t)-1;
+    int p = 0;
+    if (valid) p = c.pos[pos_offset(c, l, s, h, n)];
+    __syncthreads();
+
+    const T *kbase = (const T *)c.k;
+#pragma unroll 4
+    for (int i = 0; i < ROW16; ++i) {
+        int ci = i * kScoreTile + tid;
+        int key = ci / ROW16, part = ci % ROW16;
+        int64_t off = row_off[key];
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (off >= 0) v = reinterpret_cast<const uint4 *>(kbase + off)[part];
+        lds[key * STRIDE16 + part] = v;
+    }
+    __syncthreads();
+
+    const int64_t inst = ((int64_t)l * c.n_seqs + s) * c.n_kv_heads + h;
+    const float *__restrict__ tb = a.table + inst * (kBands * 3 * G);
+    const double *__restrict__ rev = a.band_rev;
+    const double pd = (double)p;
+    float acc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) acc[g] = 0.f;
+    const uint4 *row = lds + tid * STRIDE16;
+
+    if constexpr (sizeof(T) == 2 && PAIRS == TRI_PAIR_INTERLEAVED) {
+#pragma unroll 2
+        for (int j = 0; j < 16; ++j) {
+            uint4 q = row[j];
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int f = 4 * j + i;
+                band_update<G>(acc, tb + f * 3 * G, pd, rev[f], bf16_lo(w[i]), bf16_hi(w[i]));
+            }
+        }
+    } else if constexpr (sizeof(T) == 2) {
+#pragma unroll 2
+        for (int j = 0; j < 8; ++j) {
+            uint4 qr = row[j], qi = row[j + 8];
+            const uint32_t wr[4] = {qr.x, qr.y, qr.z, qr.w}, wi[4] = {qi.x, qi.y, qi.z, qi.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int f = 8 * j + 2 * i;
+                band_update<G>(acc, tb + f * 3 * G, pd, rev[f], bf16_lo(wr[i]), bf16_lo(wi[i]));
+                band_update<G>(acc, tb + (f + 1) * 3 * G, pd, rev[f + 1], bf16_hi(wr[i]), bf16_hi(wi[i]));
+            }
+        }
+    } else if constexpr (PAIRS == TRI_PAIR_INTERLEAVED) {
+#pragma unroll 2
+        for (int j = 0; j < 32; ++j) {
+            uint4 q = row[j];
+            int f = 2 * j;
+            band_update<G>(acc, tb + f * 3 * G, pd, rev[f], __uint_as_float(q.x), __uint_as_float(q.y));
+            band_update<G>(acc, tb + (f + 1) * 3 * G, pd, rev[f + 1], __uint_as_float(q.z), __uint_as_float(q.w));
+        }
+    } else {
+#pragma unroll 2
+        for (int j = 0; j < 16; ++j) {
+            uint4 qr = row[j], qi = row[j + 16];
+            const uint32_t wr[4] = {qr.x, qr.y, qr.z, qr.w}, wi[4] = {qi.x, qi.y, qi.z, qi.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int f = 4 * j + i;
+                band_update<G>(acc, tb + f * 3 * G, pd, rev[f], __uint_as_float(wr[i]), __uint_as_float(wi[i]));
+            }
+        }
+    }
+
+    // raw scores out, and this tile's sum / sum of squares per query head (double, fixed order)
+    const int Hq = c.n_kv_heads * G;
+    float *rw = a.raw + (((int64_t)l * c.n_seqs + s) * Hq + (int64_t)h * G) * c.max_seq_len + n;
+    double mom[2 * G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (valid) rw[(int64_t)g * c.max_seq_len] = acc[g];
+        double v = valid ? (double)acc[g] : 0.0;
+        mom[g] = v;
+        mom[G + g] = v * v;
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * G; ++i) {
+        double v = mom[i];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        mom[i] = v;
+    }
+    if ((tid & 63) == 0) {
+#pragma unroll
+        for (int i = 0; i < 2 * G; ++i) red[tid >> 6][i] = mom[i];
+    }
+    __syncthreads();
+    if (tid < 2 * G) {
+        double v = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
+        a.partials[(inst * a.n_tiles + tile) * (2 * G) + tid] = v;
+    }
+}
+
+struct StatsArgs {
+    const double *partials;
+    double *stats;  // [inst][G][2] = (mean, 1/sigma)
+    const int32_t *seq_len;
+    int32_t n_seqs, n_kv_heads, n_tiles, G;
+};
+
+// grid (instances), block 256: Section 4.3, mu_g and sigma_g over the N keys (population sigma).
+__global__ __launch_bounds__(256) void stats_kernel(StatsArgs a)
+{
+    __shared__ double part[16][16];
+    const int inst = blockIdx.x;
+    const int s = (inst / a.n_kv_heads) % a.n_seqs;
+    const int N = a.seq_len[s];
+    const int tiles = (N + kScoreTile - 1) / kScoreTile;
+    const int i = threadIdx.x & 15, r = threadIdx.x >> 4;
+    const int W = 2 * a.G;
+    double acc = 0.0;
+    if (i < W)
+        for (int t = r; t < tiles; t += 16) acc += a.partials[((int64_t)inst * a.n_tiles + t) * W + i];
+    part[r][i] = acc;
+    __syncthreads();
+    if (threadIdx.x < a.G) {
+        const int g = threadIdx.x;
+        double s1 = 0.0, s2 = 0.0;
+        for (int k = 0; k < 16; ++k) {
+            s1 += part[k][g];
+            s2 += part[k][a.G + g];
+        }
+        double mean = 0.0, rsig = 0.0;
+        if (N > 0) {
+            mean = s1 / (double)N;
+            double msq = s2 / (double)N;
+            double var = msq - mean * mean;
+            // all-equal scores leave only rounding noise here: that head then contributes 0
+            if (var > 1e-14 * msq) rsig = 1.0 / sqrt(var);
+        }
+        a.stats[((int64_t)inst * a.G + g) * 2 + 0] = mean;
+        a.stats[((int64_t)inst * a.G + g) * 2 + 1] = rsig;
+    }
+}
+
+struct FinalArgs {
+    const float *raw;     // [inst][G][Nmax]  (instance-major because Hq = Hkv * G)
+    const double *stats;  // [inst][G][2]
+    float *final_;        // [inst][Nmax]
+    const int32_t *seq_len;
+    int32_t n_seqs, n_kv_heads, max_seq_len;
+};
+
+// grid (ceil(Nmax/1024), instances), block 256: S_final(k) = max_g (S~(g)(k) - mu_g) / sigma_g.
+template <int G>
+__global__ __launch_bounds__(256) void final_kernel(FinalArgs a)
+{
+    const int inst = blockIdx.y;
+    const int s = (inst / a.n_kv_heads) % a.n_seqs;
+    const int N = a.seq_len[s];
+    const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (n >= N) return;
+    const float *rw = a.raw + (int64_t)inst * G * a.max_seq_len + n;
+    const double *st = a.stats + (int64_t)inst * G * 2;
+    float best[4];
+    if (n + 3 < N && (a.max_seq_len & 3) == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float4 v = *reinterpret_cast<const float4 *>(rw + (int64_t)g * a.max_seq_len);
+            const double mu = st[2 * g], rs = st[2 * g + 1];
+            const float z[4] = {(float)(((double)v.x - mu) * rs), (float)(((double)v.y - mu) * rs),
+                                (float)(((double)v.z - mu) * rs), (float)(((double)v.w - mu) * rs)};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) best[k] = (g == 0) ? z[k] : fmaxf(best[k], z[k]);
+        }
+        *reinterpret_cast<float4 *>(a.final_ + (int64_t)inst * a.max_seq_len + n) =
+            make_float4(best[0], best[1], best[2], best[3]);
+    } else {
+        for (int k = 0; k < 4 && n + k < N; ++k) {
+            float b = 0.f;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float z = (float)(((double)rw[(int64_t)g * a.max_seq_len + k] - st[2 * g]) * st[2 * g + 1]);
+                b = (g == 0) ? z : fmaxf(b, z);
+            }
+            a.final_[(int64_t)inst * a.max_seq_len + n + k] = b;
+        }
+    }
+}
+
+template <int G, typename T>
+tri_status launch_score_kernel(const tri_model &m, const ScoreArgs &sa, dim3 grid, hipStream_t st)
+{
+    const size_t lds = (size_t)kScoreTile * (Elem<T>::kRow16 + 1) * 16;
+    if (m.pairs == TRI_PAIR_INTERLEAVED) {
+        auto kern = score_kernel<G, T, TRI_PAIR_INTERLEAVED>;
+        if (lds > 48 * 1024 &&
+            hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return hip_status("hipFuncSetAttribute(score_kernel)");
+        hipLaunchKernelGGL(kern, grid, dim3(kScoreTile), lds, st, sa);
+    } else {
+        auto kern = score_kernel<G, T, TRI_PAIR_HALF>;
+        if (lds > 48 * 1024 &&
+            hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return hip_status("hipFuncSetAttribute(score_kernel)");
+        hipLaunchKernelGGL(kern, grid, dim3(kScoreTile), lds, st, sa);
+    }
+    return hip_status("score_kernel");
+}
+
+template <int G>
+tri_status launch_score_g(const tri_model &m, const tri_cache &c, const ScoreArgs &sa, const FinalArgs &fa,
+                          float *final_out, hipStream_t st)
+{
+    const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
+    dim3 grid(sa.n_tiles, c.n_seqs * m.n_kv_heads, m.n_layers);
+    tri_status rc = (c.dtype == TRI_BF16) ? launch_score_kernel<G, uint16_t>(m, sa, grid, st)
+                                          : launch_score_kernel<G, float>(m, sa, grid, st);
+    if (rc != TRI_OK) return rc;
+    StatsArgs ta{sa.partials, const_cast<double *>(fa.stats), c.seq_len, c.n_seqs, m.n_kv_heads, sa.n_tiles, G};
+    hipLaunchKernelGGL(stats_kernel, dim3(n_inst), dim3(256), 0, st, ta);
+    if ((rc = hip_status("stats_kernel")) != TRI_OK) return rc;
+    if (final_out) {
+        hipLaunchKernelGGL(final_kernel<G>, dim3((c.max_seq_len + 1023) / 1024, n_inst), dim3(256), 0, st, fa);
+        rc = hip_status("final_kernel");
+    }
+    return rc;
+}
+
+}  // namespace
+
+tri_status launch_score(const tri_model &m, const float *centers, const tri_cache &c, float *final_out,
+                        float *raw_out, char *ws, const Workspace &wl, hipStream_t st)
+{
+    const int G = m.n_q_heads / m.n_kv_heads;
+    if (c.max_seq_len <= 0 || c.n_seqs <= 0) return TRI_OK;
+    FoldArgs fo{};
+    fo.centers = centers;
+    fo.table = reinterpret_cast<float *>(ws + wl.table);
+    fo.band_rev = reinterpret_cast<double *>(ws + wl.band_rev);
+    fo.cur_pos = c.cur_pos;
+    fo.S = c.n_seqs;
+    fo.Hq = m.n_q_heads;
+    fo.Hkv = m.n_kv_heads;
+    fo.G = G;
+    fo.theta = m.rope_theta;
+    fo.n_off = m.n_offsets;
+    for (int j = 0; j < m.n_offsets; ++j) fo.offsets[j] = m.offsets[j];
+    hipLaunchKernelGGL(fold_kernel, dim3(m.n_q_heads, m.n_layers), dim3(kBands), 0, st, fo);
+    tri_status rc = hip_status("fold_kernel");
+    if (rc != TRI_OK) return rc;
+
+    ScoreArgs sa{};
+    sa.c = make_view(m, c);
+    sa.table = fo.table;
+    sa.band_rev = fo.band_rev;
+    sa.raw = raw_out ? raw_out : reinterpret_cast<float *>(ws + wl.raw);
+    sa.partials = reinterpret_cast<double *>(ws + wl.partials);
+    sa.n_tiles = (c.max_seq_len + kScoreTile - 1) / kScoreTile;
+    FinalArgs fa{sa.raw, reinterpret_cast<double *>(ws + wl.stats), final_out, c.seq_len, c.n_seqs,
+                 m.n_kv_heads, c.max_seq_len};
+    switch (G) {
+        case 1: return launch_score_g<1>(m, c, sa, fa, final_out, st);
+        case 2: return launch_score_g<2>(m, c, sa, fa, final_out, st);
+        case 4: return launch_score_g<4>(m, c, sa, fa, final_out, st);
+        case 8: return launch_score_g<8>(m, c, sa, fa, final_out, st);
+    }
+    set_error("group size %d not built (1, 2, 4, 8)", G);
+    return TRI_ERR_UNSUPPORTED;
+}
+
+}  // namespace tri

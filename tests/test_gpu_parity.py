@@ -1,0 +1,108 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from workload import recipe
+
+import tri_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_instance(oracle, cfg, w, stats, l, s, h, threads=8):
+    G = cfg.group
+    n = int(w["seq_len"][s])
+    return oracle.head_instance(stats[l, h * G:(h + 1) * G], w["k"][l, s, h, :n], w["pos"][l, s, h, :n],
+                                int(w["cur_pos"][s]), cfg.rope_theta, cfg.offsets, cfg.budget, threads=threads)
+
+
+def run_and_check(oracle, cfg, instances=None, paged=False, inplace=False):
+    w = recipe.generate(cfg)
+    run = H.GpuRun(cfg, w, paged=paged)
+    stats_gpu = run.build_centers()
+    stats = oracle.centers(w["q_samples"])
+    np.testing.assert_allclose(stats_gpu, stats, rtol=3e-7, atol=1e-30)
+    # score with the oracle's table so that the two sides read identical bytes
+    run.centers.copy_(torch.from_numpy(stats))
+    final, raw = run.score()
+    idx, cnt = run.select()
+    L, S, Hkv, G = cfg.n_layers, cfg.n_seqs, cfg.n_kv_heads, cfg.group
+    if instances is None:
+        instances = [(l, s, h) for l in range(L) for s in range(S) for h in range(Hkv)]
+    exact = 0
+    worst_raw = worst_final = 0.0
+    for (l, s, h) in instances:
+        n = int(w["seq_len"][s])
+        if n == 0:
+            assert cnt[l, s, h] == 0
+            continue
+        ref = oracle_instance(oracle, cfg, w, stats, l, s, h)
+        worst_raw = max(worst_raw, H.check_raw(raw[l, s, h * G:(h + 1) * G, :n], ref["raw"]))
+        worst_final = max(worst_final, H.check_final(final[l, s, h, :n], ref["final"]))
+        exact += H.check_kept(idx[l, s, h], int(cnt[l, s, h]), ref["final"], ref["idx"], n, cfg.budget)
+        # selection proper is integer work: on the GPU's own fp32 scores it must match the oracle bit for bit
+        ref_idx32 = oracle.topk(final[l, s, h, :n].astype(np.float64), cfg.budget)
+        np.testing.assert_array_equal(idx[l, s, h, :len(ref_idx32)], ref_idx32)
+    # compaction: bit-exact rows, out of place or in place
+    if inplace:
+        new_len = run.compact()
+        k_out, v_out, p_out = H.to_numpy(run.k), H.to_numpy(run.v), run.pos.cpu().numpy()
+    else:
+        kd, vd, pd = torch.zeros_like(run.k), torch.zeros_like(run.v), torch.zeros_like(run.pos)
+        dst = run.B.Cache(kd, vd, pd, run.seq_len, run.cur_pos, run.nmax, run.block_table)
+        new_len = run.compact(dst)
+        k_out, v_out, p_out = H.to_numpy(kd), H.to_numpy(vd), pd.cpu().numpy()
+    np.testing.assert_array_equal(new_len, np.minimum(w["seq_len"], cfg.budget))
+    for (l, s, h) in instances:
+        c = int(cnt[l, s, h])
+        sel = idx[l, s, h, :c]
+        if paged:
+            bs = cfg.block_size
+            strides = (run.k.stride(0), run.k.stride(1), run.k.stride(2), run.k.stride(3))
+            pstr = (run.pos.stride(0), run.pos.stride(1), run.pos.stride(2), 1)
+            got_k = oracle.paged_gather(k_out, cfg.head_dim, run.bt_np, bs, strides, l, s, h, c)
+            got_v = oracle.paged_gather(v_out, cfg.head_dim, run.bt_np, bs, strides, l, s, h, c)
+            got_p = oracle.paged_gather(p_out, 1, run.bt_np, bs, pstr, l, s, h, c)[:, 0]
+        else:
+            got_k, got_v, got_p = k_out[l, s, h, :c], v_out[l, s, h, :c], p_out[l, s, h, :c]
+        np.testing.assert_array_equal(got_k, oracle.compact_rows(w["k"][l, s, h], sel))
+        np.testing.assert_array_equal(got_v, oracle.compact_rows(w["v"][l, s, h], sel))
+        np.testing.assert_array_equal(got_p, w["pos"][l, s, h][sel])
+    print("\n[%s] instances %d, identical index sets %d, worst raw err %.2e (rel), worst final err %.2e"
+          % (cfg.name, len(instances), exact, worst_raw, worst_final), flush=True)
+    return exact, len(instances)
+
+
+def test_c1_tiny_fp32(oracle):
+    """Config 1 in full: 1 KV head, 4 query heads, N = 4096 dense positions, B = 512, fp32."""
+    run_and_check(oracle, recipe.CONFIGS["c1_tiny"])
+
+
+def test_small_bf16_ragged_sparse(oracle):
+    """Qwen3-shaped heads at small N: several tiles and a ragged tail, sparse positions, two layers,
+    three sequences of different lengths (one shorter than the budget, one empty)."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=2, n_seqs=3, n_q_heads=8, n_kv_heads=2, seq_len=1000,
+                        min_seq_len=0, budget=200, n_calib=256)
+    w_len = recipe.seq_lens(cfg)
+    assert len(set(w_len.tolist())) == 3
+    run_and_check(oracle, cfg)
+
+
+def test_small_inplace(oracle):
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=2, n_q_heads=8, n_kv_heads=2, seq_len=777,
+                        min_seq_len=300, budget=128, n_calib=128)
+    run_and_check(oracle, cfg, inplace=True)
+
+
+@pytest.mark.parametrize("inplace", [False, True])
+def test_small_paged(oracle, inplace):
+    cfg = recipe.scaled(recipe.CONFIGS["c4_paged"], n_layers=2, n_seqs=3, n_q_heads=8, n_kv_heads=2, seq_len=900,
+                        min_seq_len=100, budget=160, n_calib=128)
+    run_and_check(oracle, cfg, paged=True, inplace=inplace)
+
+
+def test_group_of_eight(oracle):
+    cfg = recipe.scaled(recipe.CONFIGS["c5_long"], n_layers=1, n_seqs=1, n_q_heads=16, n_kv_heads=2, seq_len=600,
+                        budget=100, n_calib=128)
+    run_and_check(oracle, cfg)

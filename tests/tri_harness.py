@@ -1,0 +1,132 @@
+"""Shared plumbing for the GPU parity tests: numpy workload -> torch tensors -> C ABI -> numpy,
+and the comparison rules (tolerances) used everywhere."""
+import numpy as np
+import torch
+
+from workload import recipe
+
+RAW_RTOL = 1e-3      # raw score: |gpu - ref| <= RAW_RTOL * max(|ref|, rms(ref))
+FINAL_RTOL = 1e-3    # final score (unit scale by construction): <= FINAL_RTOL * max(|ref|, 1)
+GAP_RTOL = 1e-3      # index sets must be identical when the B-th and (B+1)-th oracle scores differ by more
+
+
+def to_torch(a, dtype, device="cuda"):
+    """numpy storage array (uint16 bf16 bits or float32) -> torch tensor on the device."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def to_numpy(t):
+    """torch tensor -> numpy storage array (bf16 comes back as uint16 bit patterns)."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+class GpuRun:
+    """One workload resident on the GPU with the buffers the four entry points need."""
+
+    def __init__(self, cfg, w, paged=False, pairs=0):
+        from paper_2604_04921_amd import binding as B
+        self.B = B
+        self.cfg = cfg
+        dev = "cuda"
+        self.model = B.Model(cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rope_theta, cfg.offsets,
+                             pairs)
+        self.q = to_torch(w["q_samples"], cfg.dtype)
+        self.seq_len = torch.from_numpy(w["seq_len"]).to(dev)
+        self.cur_pos = torch.from_numpy(w["cur_pos"]).to(dev)
+        self.block_table = None
+        if paged:
+            bt, nb = recipe.paged_layout(cfg, w["seq_len"])
+            self.bt_np, self.n_blocks = bt, nb
+            self.k = to_torch(recipe.to_paged(w["k"], w["seq_len"], bt, nb, cfg.block_size), cfg.dtype)
+            self.v = to_torch(recipe.to_paged(w["v"], w["seq_len"], bt, nb, cfg.block_size), cfg.dtype)
+            self.pos = torch.from_numpy(recipe.to_paged(w["pos"][..., None], w["seq_len"], bt, nb, cfg.block_size)[..., 0].copy()).to(dev)
+            self.block_table = torch.from_numpy(bt).to(dev)
+        else:
+            self.k = to_torch(w["k"], cfg.dtype)
+            self.v = to_torch(w["v"], cfg.dtype)
+            self.pos = torch.from_numpy(w["pos"]).to(dev)
+        self.nmax = int(cfg.seq_len)
+        self.cache = B.Cache(self.k, self.v, self.pos, self.seq_len, self.cur_pos, self.nmax, self.block_table)
+        L, S, Hq, Hkv = cfg.n_layers, cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads
+        self.centers = torch.empty((L, Hq, cfg.n_bands, 3), dtype=torch.float32, device=dev)
+        self.final = torch.full((L, S, Hkv, self.nmax), float("nan"), dtype=torch.float32, device=dev)
+        self.raw = torch.full((L, S, Hq, self.nmax), float("nan"), dtype=torch.float32, device=dev)
+        self.kept_idx = torch.full((L, S, Hkv, cfg.budget), -1, dtype=torch.int32, device=dev)
+        self.kept_cnt = torch.full((L, S, Hkv), -1, dtype=torch.int32, device=dev)
+        self.new_len = torch.full((S,), -1, dtype=torch.int32, device=dev)
+        ws = B.tri_workspace_size(self.model, self.cache, cfg.budget)
+        assert ws > 0
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=dev)
+
+    def build_centers(self):
+        self.B.tri_build_centers(self.model, self.q, self.centers)
+        torch.cuda.synchronize()
+        return self.centers.cpu().numpy()
+
+    def score(self, want_raw=True):
+        self.B.tri_score(self.model, self.centers, self.cache, self.final, self.raw if want_raw else None, self.ws)
+        torch.cuda.synchronize()
+        return self.final.cpu().numpy(), (self.raw.cpu().numpy() if want_raw else None)
+
+    def select(self, final=None):
+        self.B.tri_select_topk(self.model, self.final if final is None else final, self.cache, self.cfg.budget,
+                               self.kept_idx, self.kept_cnt, self.ws)
+        torch.cuda.synchronize()
+        return self.kept_idx.cpu().numpy(), self.kept_cnt.cpu().numpy()
+
+    def compact(self, dst_cache=None):
+        self.B.tri_compact(self.model, self.cache, self.cache if dst_cache is None else dst_cache, self.cfg.budget,
+                           self.kept_idx, self.kept_cnt, self.new_len)
+        torch.cuda.synchronize()
+        return self.new_len.cpu().numpy()
+
+
+def check_raw(gpu, ref):
+    """gpu, ref [G][N]; returns the worst error in units of the tolerance."""
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = np.sqrt(np.mean(ref ** 2, axis=1, keepdims=True))
+    tol = RAW_RTOL * np.maximum(np.abs(ref), rms)
+    err = np.abs(gpu.astype(np.float64) - ref)
+    assert np.all(np.isfinite(gpu))
+    worst = float(np.max(err / tol))
+    assert worst <= 1.0, "raw score off by %.3g x tolerance" % worst
+    return worst * RAW_RTOL
+
+
+def check_final(gpu, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    tol = FINAL_RTOL * np.maximum(np.abs(ref), 1.0)
+    err = np.abs(gpu.astype(np.float64) - ref)
+    assert np.all(np.isfinite(gpu))
+    worst = float(np.max(err / tol))
+    assert worst <= 1.0, "final score off by %.3g x tolerance" % worst
+    return worst * FINAL_RTOL
+
+
+def check_kept(idx, cnt, ref_final, ref_idx, N, B):
+    """Index-set rule.  Always: count, ascending, unique, in range, and the band rule (every kept key's
+    oracle score >= tau - eps, every dropped key's <= tau + eps, tau the B-th oracle score).  When the
+    oracle's B-th and (B+1)-th scores differ by more than GAP_RTOL relative the sets must be identical.
+    Returns True when the set is identical to the oracle's."""
+    keep = min(N, B)
+    assert cnt == keep
+    got = idx[:keep]
+    assert np.all(got[1:] > got[:-1]) and (keep == 0 or (got[0] >= 0 and got[-1] < N))
+    same = np.array_equal(got, ref_idx)
+    if N <= B:
+        assert same
+        return True
+    order = np.sort(ref_final)[::-1]
+    tau, nxt = order[B - 1], order[B]
+    eps = GAP_RTOL * max(abs(tau), 1.0)
+    kept_mask = np.zeros(N, dtype=bool)
+    kept_mask[got] = True
+    assert np.all(ref_final[kept_mask] >= tau - eps)
+    assert np.all(ref_final[~kept_mask] <= tau + eps)
+    if tau - nxt > GAP_RTOL * max(abs(tau), abs(nxt)):
+        assert same, "index set differs although the oracle's gap at the budget is wide"
+    return same
