@@ -172,7 +172,7 @@ def paged_layout(cfg: Config, lens, seed_tag=8):
     need = [-(-int(n) // bs) for n in lens]
     n_blocks = int(sum(need))
     perm = _rng(cfg.seed, seed_tag).permutation(n_blocks).astype(np.int32)
-    mb = max(need)
+    mb = max(max(need), -(-int(cfg.seq_len) // bs))   # the table spans the configured maximum length
     bt = np.zeros((len(lens), mb), dtype=np.int32)
     o = 0
     for s, nb in enumerate(need):
