@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the TriAttention KV-cache compression step on one MI355X.
+
+One "step" = score -> GQA reduce -> top-B -> compact over the whole synthetic batch (all layers,
+sequences and KV heads of the configuration), inputs resident in HBM.  Prints ONE JSON line:
+throughput in cached keys per second, the roofline of the dominant (score) kernel measured with HIP
+events inside the timed region, and the CPU oracle timed on a bounded sample on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+SCORE_BYTES_PER_KEY = 260      # one bf16 K row (2*128 B) + one int32 position, read once
+STEP_BYTES = lambda n, b: 260 * n + 1032 * min(n, b)   # + survivors' K, V, pos read and written
+
+# HBM traffic of one score-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by
+# a copy kernel of known size); see profiles/.  None until measured for that workload.
+MEASURED_TRAFFIC = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="c3_model")
+    ap.add_argument("--positions", default=None, choices=[None, "dense", "sparse"])
+    ap.add_argument("--layers", type=int, default=None, help="layer slab (configurations larger than HBM)")
+    ap.add_argument("--cpu-instances", type=int, default=4, help="head-instances the CPU oracle is timed on")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--split", action="store_true", help="call the three entry points instead of the fused one")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_04921_amd import binding as T
+    from workload import device, recipe
+
+    cfg = recipe.CONFIGS[args.config]
+    mode = args.positions or cfg.positions
+    L = args.layers or cfg.n_layers
+    dev = "cuda"
+    t_gen = time.time()
+    w = device.generate(cfg, positions=mode, layers=L)
+    S, Hq, Hkv, B, d = cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads, cfg.budget, cfg.head_dim
+    model = T.Model(L, Hq, Hkv, d, cfg.rope_theta, cfg.offsets)
+    src = T.Cache(w["k"], w["v"], w["pos"], w["seq_len"], w["cur_pos"], cfg.seq_len, w.get("block_table"))
+    centers = torch.empty((L, Hq, d // 2, 3), dtype=torch.float32, device=dev)
+    T.tri_build_centers(model, w["q_samples"], centers)
+    paged = "block_table" in w
+    if paged:   # in place: the survivors go to the front blocks of the same pools
+        dst = src
+    else:
+        kd = torch.empty((L, S, Hkv, B, d), dtype=w["k"].dtype, device=dev)
+        vd = torch.empty_like(kd)
+        pd = torch.empty((L, S, Hkv, B), dtype=torch.int32, device=dev)
+        dst = T.Cache(kd, vd, pd, w["seq_len"], w["cur_pos"], B)
+    kept_idx = torch.empty((L, S, Hkv, B), dtype=torch.int32, device=dev)
+    kept_cnt = torch.empty((L, S, Hkv), dtype=torch.int32, device=dev)
+    new_len = torch.empty((S,), dtype=torch.int32, device=dev)
+    ws = torch.empty(T.tri_workspace_size(model, src, B), dtype=torch.uint8, device=dev)
+    final = torch.empty((L, S, Hkv, cfg.seq_len), dtype=torch.float32, device=dev) if args.split else None
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    def step():
+        if args.split:
+            T.tri_score(model, centers, src, final, None, ws)
+            T.tri_select_topk(model, final, src, B, kept_idx, kept_cnt, ws)
+            T.tri_compact(model, src, dst, B, kept_idx, kept_cnt, new_len)
+        else:
+            T.tri_compress_step(model, centers, src, dst, B, kept_idx, kept_cnt, new_len, ws)
+
+    # how many score-kernel launches one step makes (the hook brackets each of them)
+    probe = [torch.cuda.Event(enable_timing=True) for _ in range(2 * 256)]
+    for e in probe:
+        e.record()
+    torch.cuda.synchronize()
+    keep = T.tri_timing_attach(probe)
+    step()
+    launches = T.tri_timing_detach()
+    torch.cuda.synchronize()
+    for _ in range(max(0, args.warmup - 1)):
+        step()
+    torch.cuda.synchronize()
+
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * launches * args.steps)]
+    for e in events:
+        e.record()
+    torch.cuda.synchronize()
+    keep = T.tri_timing_attach(events)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    got = T.tri_timing_detach()
+    assert got == launches * args.steps, (got, launches, args.steps)
+    del keep
+
+    lens = w["seq_len"].cpu().numpy().astype(np.int64)
+    keys = int(lens.sum()) * L * Hkv
+    ms = (t1 - t0) * 1e3 / args.steps
+    value = keys / (ms * 1e-3) / 1e9
+    k_ms = [events[2 * i].elapsed_time(events[2 * i + 1]) for i in range(launches * args.steps)]
+    launch_ms = float(np.mean(k_ms))
+    eb = 2 if cfg.dtype == "bf16" else 4
+    bytes_per_launch = (eb * d + 4) * keys / launches
+    achieved = bytes_per_launch / (launch_ms * 1e-3) / 1e9
+    step_bytes = int(sum(STEP_BYTES(int(n), B) for n in lens)) * L * Hkv if eb == 2 else None
+    roofline = {"bound": "hbm", "kernel": "score_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC.get("%s/%s" % (cfg.name, mode)),
+                "launch_ms": round(launch_ms, 4), "launches_per_step": launches,
+                "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+    if step_bytes:
+        roofline["step_gbs"] = round(step_bytes / (ms * 1e-3) / 1e9, 1)
+        roofline["step_frac"] = round(step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, args.cpu_instances, paged)
+
+    out = {"metric": "cached keys scored+selected+compacted per second", "value": round(value, 3), "unit": "Gkeys/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": cfg.name, "positions": mode, "layers": L, "seqs": S, "kv_heads": Hkv,
+                      "q_heads": Hq, "head_dim": d, "keys_per_seq": cfg.seq_len, "budget": B,
+                      "n_offsets": cfg.n_offsets, "storage": cfg.dtype, "layout": "paged16" if paged else "contiguous",
+                      "keys": keys, "entry": "split" if args.split else "tri_compress_step",
+                      "generate_s": round(t_gen, 1)},
+           "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, n_inst, paged):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: whole head-instances spread
+    over layers and sequences, copied back from the device.  Also confirms the GPU's kept sets on them."""
+    import numpy as np
+    import torch
+    from oracle import tri_oracle as O
+    from workload import recipe
+
+    S, Hkv, G = cfg.n_seqs, cfg.n_kv_heads, cfg.group
+    stats = centers.cpu().numpy()
+    lens = w["seq_len"].cpu().numpy()
+    cur = w["cur_pos"].cpu().numpy()
+    picks = [((i * (L - 1)) // max(1, n_inst - 1) if n_inst > 1 else 0, (i * 5) % S, (i * 3) % Hkv) for i in range(n_inst)]
+    threads = min(16, os.cpu_count() or 1)
+    jobs = []
+    for (l, s, h) in picks:
+        n = int(lens[s])
+        if paged:
+            bs = cfg.block_size
+            bt = w["block_table"][s, : -(-n // bs)].long()
+            k = w["k"][l, bt, h].reshape(-1, cfg.head_dim)[:n]
+            p = w["pos"][l, bt, h].reshape(-1)[:n]
+        else:
+            k, p = w["k"][l, s, h, :n], w["pos"][l, s, h, :n]
+        kn = k.contiguous().view(torch.int16).cpu().numpy().view(np.uint16) if k.dtype == torch.bfloat16 else k.cpu().numpy()
+        jobs.append((stats[l, h * G:(h + 1) * G], kn, p.cpu().numpy(), int(cur[s])))
+    O.lib()
+    t0 = time.perf_counter()
+    res = [O.head_instance(st, kn, p, c, cfg.rope_theta, cfg.offsets, cfg.budget, threads=threads)
+           for (st, kn, p, c) in jobs]
+    dt = time.perf_counter() - t0
+    nkeys = sum(j[1].shape[0] for j in jobs)
+    same = 0
+    for (l, s, h), r in zip(picks, res):
+        c = int(kept_cnt[l, s, h])
+        same += int(np.array_equal(kept_idx[l, s, h, :c].cpu().numpy(), r["idx"]))
+    return {"value": round(nkeys / dt / 1e9, 9), "unit": "Gkeys/s", "cores": threads, "kind": "oracle",
+            "sample": "%d whole head-instances (%d keys) spread over layers/sequences, score+reduce+select; "
+                      "compaction is a memcpy and is left out" % (len(jobs), nkeys),
+            "seconds": round(dt, 2), "kept_sets_identical_to_gpu": "%d/%d" % (same, len(jobs))}
+
+
+if __name__ == "__main__":
+    main()

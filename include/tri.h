@@ -157,6 +157,17 @@ tri_status tri_compress_step(const tri_model *model, const float *centers, const
                              int32_t *kept_cnt, int32_t *new_seq_len, void *workspace,
                              size_t ws_bytes, void *stream);
 
+/*
+ * Measurement hook for benchmark harnesses (no counterpart in the paper).  After attaching, the
+ * i-th launch of the score kernel made by the calling thread (i = 0, 1, ...) is bracketed by
+ * hipEventRecord(events[2i]) before and hipEventRecord(events[2i+1]) after it, on the stream of
+ * that launch, until n_pairs launches have been bracketed.  `events` is a HOST array of
+ * 2*n_pairs hipEvent_t created by the caller with timing enabled; it must stay valid until
+ * tri_timing_detach(), which returns the number of launches bracketed since the attach.
+ */
+tri_status tri_timing_attach(void **events, int32_t n_pairs);
+int32_t tri_timing_detach(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ TRI_F32, TRI_BF16 = 0, 1
 TRI_PAIR_INTERLEAVED, TRI_PAIR_HALF = 0, 1
 
 EXPORTS = ["tri_last_error", "tri_build_centers", "tri_workspace_size", "tri_score", "tri_select_topk",
-           "tri_compact", "tri_compress_step"]
+           "tri_compact", "tri_compress_step", "tri_timing_attach", "tri_timing_detach"]
 
 
 class TriModel(ctypes.Structure):
@@ -72,6 +72,10 @@ def lib():
         L.tri_compress_step.restype = i32
         L.tri_compress_step.argtypes = [ctypes.POINTER(TriModel), vp, ctypes.POINTER(TriCache),
                                         ctypes.POINTER(TriCache), i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.tri_timing_attach.restype = i32
+        L.tri_timing_attach.argtypes = [vp, i32]
+        L.tri_timing_detach.restype = i32
+        L.tri_timing_detach.argtypes = []
         _lib = L
     return _lib
 
@@ -170,3 +174,15 @@ def tri_compress_step(model, centers, src, dst, budget, kept_idx, kept_cnt, new_
     _check(lib().tri_compress_step(model.ref, _p(centers), src.ref, dst.ref, int(budget), _p(kept_idx), _p(kept_cnt),
                                    _p(new_seq_len), _p(workspace), workspace.numel() * workspace.element_size(),
                                    _stream(stream)))
+
+
+def tri_timing_attach(events):
+    """events: list of torch.cuda.Event (timing enabled, each recorded once before so that its handle exists),
+    laid out start0, stop0, start1, stop1, ...  Returns the ctypes array that must be kept alive until detach."""
+    arr = (ctypes.c_void_p * len(events))(*[e.cuda_event for e in events])
+    _check(lib().tri_timing_attach(arr, len(events) // 2))
+    return arr
+
+
+def tri_timing_detach():
+    return int(lib().tri_timing_detach())

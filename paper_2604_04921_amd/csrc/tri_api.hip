@@ -16,6 +16,18 @@ void set_error(const char *fmt, ...)
     va_end(ap);
 }
 
+static thread_local void **g_events = nullptr;
+static thread_local int32_t g_event_pairs = 0, g_event_next = 0;
+
+bool timing_next(hipEvent_t *start, hipEvent_t *stop)
+{
+    if (!g_events || g_event_next >= g_event_pairs) return false;
+    *start = (hipEvent_t)g_events[2 * g_event_next];
+    *stop = (hipEvent_t)g_events[2 * g_event_next + 1];
+    ++g_event_next;
+    return true;
+}
+
 tri_status hip_status(const char *what)
 {
     hipError_t e = hipGetLastError();
@@ -175,6 +187,26 @@ using namespace tri;
 extern "C" {
 
 const char *tri_last_error(void) { return g_error; }
+
+tri_status tri_timing_attach(void **events, int32_t n_pairs)
+{
+    if (n_pairs < 0 || (n_pairs > 0 && !events)) {
+        set_error("tri_timing_attach: events required for n_pairs > 0");
+        return TRI_ERR_INVALID_ARG;
+    }
+    g_events = n_pairs > 0 ? events : nullptr;
+    g_event_pairs = n_pairs;
+    g_event_next = 0;
+    return TRI_OK;
+}
+
+int32_t tri_timing_detach(void)
+{
+    const int32_t n = g_event_next;
+    g_events = nullptr;
+    g_event_pairs = g_event_next = 0;
+    return n;
+}
 
 tri_status tri_build_centers(const tri_model *model, const void *q_samples, int32_t q_dtype, int64_t n_tokens,
                              float *centers_out, void *stream)

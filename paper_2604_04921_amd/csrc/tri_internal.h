@@ -66,6 +66,8 @@ tri_status check_model(const tri_model *m);
 tri_status check_cache(const tri_model *m, const tri_cache *c, bool need_v, const char *what);
 CacheView make_view(const tri_model &m, const tri_cache &c);
 tri_status hip_status(const char *what);
+// timing hook: the next event pair to record around a score-kernel launch, if any is attached
+bool timing_next(hipEvent_t *start, hipEvent_t *stop);
 
 // launchers (each validates nothing; the entry points in tri_api.hip do)
 tri_status launch_centers(const tri_model &m, const void *q, int32_t q_dtype, int64_t n_tokens,

@@ -342,8 +342,12 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, const ScoreArg
 {
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
     dim3 grid(sa.n_tiles, c.n_seqs * m.n_kv_heads, m.n_layers);
+    hipEvent_t ev0, ev1;
+    const bool timed = timing_next(&ev0, &ev1);
+    if (timed) (void)hipEventRecord(ev0, st);
     tri_status rc = (c.dtype == TRI_BF16) ? launch_score_kernel<G, uint16_t>(m, sa, grid, st)
                                           : launch_score_kernel<G, float>(m, sa, grid, st);
+    if (timed) (void)hipEventRecord(ev1, st);
     if (rc != TRI_OK) return rc;
     StatsArgs ta{sa.partials, const_cast<double *>(fa.stats), c.seq_len, c.n_seqs, m.n_kv_heads, sa.n_tiles, G};
     hipLaunchKernelGGL(stats_kernel, dim3(n_inst), dim3(256), 0, st, ta);
