@@ -157,6 +157,8 @@ Workspace workspace_layout(const tri_model &m, const tri_cache &c, int32_t budge
     size_t o = 0;
     w.band_rev = o;
     o = align256(o + kBands * sizeof(double));
+    w.phasors = o;
+    o = align256(o + 128 * 1024);
     w.table = o;
     o = align256(o + inst * kBands * 3 * G * sizeof(float));
     w.partials = o;

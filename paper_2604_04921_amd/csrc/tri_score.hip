@@ -9,7 +9,7 @@
 // The fold kernel builds (Re Qhat, Im Qhat, c) per (layer, sequence, query head, band) in double;
 // the score kernel then needs, per key and band, one rotation of the key by its own position,
 // one modulus, and three FMAs per query head -- independent of |D|.
-#include "tri_internal.h"
+#include "tri_score_common.h"
 
 namespace tri {
 
@@ -67,15 +67,6 @@ __global__ __launch_bounds__(kBands) void fold_kernel(FoldArgs a)
     }
 }
 
-struct ScoreArgs {
-    CacheView c;
-    const float *table;
-    const double *band_rev;
-    float *raw;        // [L][S][Hq][Nmax]
-    double *partials;  // [L][S][Hkv][n_tiles][2G]
-    int32_t n_tiles;
-};
-
 template <typename T>
 struct Elem;
 template <>
@@ -86,9 +77,6 @@ template <>
 struct Elem<uint16_t> {
     static constexpr int kRow16 = 16;
 };
-
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 // One band of one key: rotate the key by its own position, take its modulus, and add the
 // three products per query head.  tb points at this band's [3][G] table entries (wave-uniform).
@@ -233,7 +221,7 @@ struct StatsArgs {
     const double *partials;
     double *stats;  // [inst][G][2] = (mean, 1/sigma)
     const int32_t *seq_len;
-    int32_t n_seqs, n_kv_heads, n_tiles, G;
+    int32_t n_seqs, n_kv_heads, n_tiles, G, tile_keys;
 };
 
 // grid (instances), block 256: Section 4.3, mu_g and sigma_g over the N keys (population sigma).
@@ -243,7 +231,7 @@ __global__ __launch_bounds__(256) void stats_kernel(StatsArgs a)
     const int inst = blockIdx.x;
     const int s = (inst / a.n_kv_heads) % a.n_seqs;
     const int N = a.seq_len[s];
-    const int tiles = (N + kScoreTile - 1) / kScoreTile;
+    const int tiles = (N + a.tile_keys - 1) / a.tile_keys;
     const int i = threadIdx.x & 15, r = threadIdx.x >> 4;
     const int W = 2 * a.G;
     double acc = 0.0;
@@ -337,19 +325,29 @@ tri_status launch_score_kernel(const tri_model &m, const ScoreArgs &sa, dim3 gri
 }
 
 template <int G>
-tri_status launch_score_g(const tri_model &m, const tri_cache &c, const ScoreArgs &sa, const FinalArgs &fa,
+tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, const FinalArgs &fa,
                           float *final_out, hipStream_t st)
 {
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
-    dim3 grid(sa.n_tiles, c.n_seqs * m.n_kv_heads, m.n_layers);
+    const bool fast = c.dtype == TRI_BF16 && m.pairs == TRI_PAIR_INTERLEAVED;
+    const int tile_keys = fast ? kFastChunk : kScoreTile;
+    sa.n_tiles = (c.max_seq_len + tile_keys - 1) / tile_keys;
+    tri_status rc = TRI_OK;
+    if (fast && (rc = launch_phasor_table(m.rope_theta, const_cast<uint4 *>(sa.phasors), st)) != TRI_OK) return rc;
     hipEvent_t ev0, ev1;
     const bool timed = timing_next(&ev0, &ev1);
     if (timed) (void)hipEventRecord(ev0, st);
-    tri_status rc = (c.dtype == TRI_BF16) ? launch_score_kernel<G, uint16_t>(m, sa, grid, st)
-                                          : launch_score_kernel<G, float>(m, sa, grid, st);
+    if (fast) {
+        rc = launch_score_fast(G, sa, m.n_layers, st);
+    } else {
+        dim3 grid(sa.n_tiles, c.n_seqs * m.n_kv_heads, m.n_layers);
+        rc = (c.dtype == TRI_BF16) ? launch_score_kernel<G, uint16_t>(m, sa, grid, st)
+                                   : launch_score_kernel<G, float>(m, sa, grid, st);
+    }
     if (timed) (void)hipEventRecord(ev1, st);
     if (rc != TRI_OK) return rc;
-    StatsArgs ta{sa.partials, const_cast<double *>(fa.stats), c.seq_len, c.n_seqs, m.n_kv_heads, sa.n_tiles, G};
+    StatsArgs ta{sa.partials, const_cast<double *>(fa.stats), c.seq_len, c.n_seqs, m.n_kv_heads, sa.n_tiles, G,
+                 tile_keys};
     hipLaunchKernelGGL(stats_kernel, dim3(n_inst), dim3(256), 0, st, ta);
     if ((rc = hip_status("stats_kernel")) != TRI_OK) return rc;
     if (final_out) {
@@ -388,7 +386,7 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     sa.band_rev = fo.band_rev;
     sa.raw = raw_out ? raw_out : reinterpret_cast<float *>(ws + wl.raw);
     sa.partials = reinterpret_cast<double *>(ws + wl.partials);
-    sa.n_tiles = (c.max_seq_len + kScoreTile - 1) / kScoreTile;
+    sa.phasors = reinterpret_cast<const uint4 *>(ws + wl.phasors);
     FinalArgs fa{sa.raw, reinterpret_cast<double *>(ws + wl.stats), final_out, c.seq_len, c.n_seqs,
                  m.n_kv_heads, c.max_seq_len};
     switch (G) {

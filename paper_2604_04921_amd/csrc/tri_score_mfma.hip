@@ -1,0 +1,295 @@
+// Score kernel for bf16 keys with interleaved pairs: fp32 MFMA for the contraction over
+// (band, component) x query head, a phasor table in LDS for the rotation of the key.
+//
+// Lane layout (wave64): lane = 4*b + i.  In one step a wave scores 4 keys; lane (b, i) loads the
+// 16 bytes holding bands 4b..4b+3 of key i -- exactly the operand layout of
+// v_mfma_f32_4x4x1_16b_f32, whose block b multiplies a 4x1 column (rows = keys i) by a 1x4 row
+// (columns = query heads j).  Per band the lane produces the rotated key (Re, Im) and the modulus
+// and feeds each as an A operand; the B operand is the lane's own table entry (band, component,
+// head j = lane % 4), held in registers.  Twelve MFMAs accumulate the lane's four bands; the sixteen
+// blocks are then summed with two lane swaps and two row rotations.
+//
+// Rotation of the key (Sections 4.1-4.2, Appendix B.2): k e^{i w p} = (k e^{i w r}) e^{i w base}
+// with r = p - base in [0, R).  e^{i w r} comes from a table in LDS (one 16-byte read per two
+// bands); e^{-i w base} is folded into the lane's table registers whenever the wave moves its base.
+// A step whose four keys span R positions or more takes the direct path instead (phase in double,
+// v_sin_f32 / v_cos_f32), so any position layout is handled.
+#include "tri_score_common.h"
+
+namespace tri {
+
+namespace {
+
+constexpr double kTwoPi = 6.283185307179586476925286766559;
+constexpr int kFastThreads = 512;
+constexpr int kFastWaves = kFastThreads / 64;
+constexpr int kWaveKeys = kFastChunk / kFastWaves;   // contiguous keys per wave
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+// grid (2*16*R / 256), block 256: entry (half hf, chunk b, r) = (cos, sin) of bands 4b+2hf, 4b+2hf+1
+// at relative position r, in double, stored at byte hf*HalfStride + b*BlockStride + 16*r.
+__global__ __launch_bounds__(256) void phasor_table_kernel(double theta, float4 *out)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int r = t % kPhasorRange, b = (t / kPhasorRange) % 16, hf = t / (kPhasorRange * 16);
+    if (hf >= 2) return;
+    float v[4];
+    for (int k = 0; k < 2; ++k) {
+        const int f = 4 * b + 2 * hf + k;
+        double x = (double)r * (pow(theta, -2.0 * (double)f / (double)kHeadDim) / kTwoPi);
+        x -= floor(x);
+        double s, c;
+        sincos(kTwoPi * x, &s, &c);
+        v[2 * k] = (float)c;
+        v[2 * k + 1] = (float)s;
+    }
+    out[(hf * kPhasorHalfStride + b * kPhasorBlockStride) / 16 + r] = make_float4(v[0], v[1], v[2], v[3]);
+}
+
+__device__ __forceinline__ float row_ror_add(float c, int ctrl_is_8)
+{
+    const int v = __float_as_int(c);
+    const int r = ctrl_is_8 ? __builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false)
+                            : __builtin_amdgcn_update_dpp(0, v, 0x124, 0xf, 0xf, false);
+    return c + __int_as_float(r);
+}
+
+// Sum the 16 blocks of a 4x4x1 accumulator.  In: lane (b, j) reg i = partial of (key i, head j) over
+// the lane's 4 bands.  Out: every lane of row r (lanes 16r..16r+15) with lane % 4 = j holds the
+// total of (key r, head j).
+__device__ __forceinline__ float reduce_blocks(float4v acc)
+{
+    auto s02 = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[0]), __float_as_uint(acc[2]), false, false);
+    auto s13 = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[1]), __float_as_uint(acc[3]), false, false);
+    // lanes < 32: keys 0 / 1 summed over both halves; lanes >= 32: keys 2 / 3
+    const float a0 = __uint_as_float(s02[0]) + __uint_as_float(s02[1]);
+    const float a1 = __uint_as_float(s13[0]) + __uint_as_float(s13[1]);
+    auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(a0), __float_as_uint(a1), false, false);
+    float c = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);   // row r now holds key r
+    c = row_ror_add(c, 1);
+    c = row_ror_add(c, 0);
+    return c;
+}
+
+// The lane's slice of the folded centre table for one group of four query heads.
+struct LaneTable {
+    float qr[4], qi[4];   // Re / Im of Qhat for bands 4b..4b+3 (absolute: p_q folded in, no base)
+    float rr[4], ri[4];   // the same rotated by e^{-i w base}: what the MFMAs consume
+    float cn[4];          // norm-term weight
+};
+
+template <int NG>
+__device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4], const float (&sn)[4],
+                                           const LaneTable (&tb)[NG], float (&out)[NG])
+{
+    const uint32_t w[4] = {kd.x, kd.y, kd.z, kd.w};
+    float4v acc[NG];
+#pragma unroll
+    for (int q = 0; q < NG; ++q) acc[q] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float re = bf16_lo(w[k]), im = bf16_hi(w[k]);
+        const float kr = re * cs[k] - im * sn[k];
+        const float ki = re * sn[k] + im * cs[k];
+        const float m = __builtin_amdgcn_sqrtf(re * re + im * im);
+#pragma unroll
+        for (int q = 0; q < NG; ++q) {
+            acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(kr, tb[q].rr[k], acc[q], 0, 0, 0);
+            acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(ki, tb[q].ri[k], acc[q], 0, 0, 0);
+            acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(m, tb[q].cn[k], acc[q], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < NG; ++q) out[q] = reduce_blocks(acc[q]);
+}
+
+// grid (ceil(Nmax / kFastChunk), S*Hkv, L), block 512.  Each wave walks kWaveKeys contiguous keys.
+template <int G>
+__global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
+{
+    constexpr int NG = (G + 3) / 4;
+    extern __shared__ uint4 lds_phasors[];
+    __shared__ double red[kFastWaves][2 * 4 * NG];
+
+    const CacheView &c = a.c;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = lane >> 2, i = lane & 3;
+    const int chunk = blockIdx.x;
+    const int s = blockIdx.y / c.n_kv_heads, h = blockIdx.y % c.n_kv_heads;
+    const int l = blockIdx.z;
+    const int N = c.seq_len[s];
+    if (chunk * kFastChunk >= N) return;   // uniform over the workgroup
+
+    for (int k = tid; k < kPhasorBytes / 16; k += kFastThreads) lds_phasors[k] = a.phasors[k];
+
+    const int64_t inst = ((int64_t)l * c.n_seqs + s) * c.n_kv_heads + h;
+    const float *tbl = a.table + inst * (kBands * 3 * G);
+    LaneTable tb[NG];
+    double rev[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int f = 4 * b + k;
+        rev[k] = a.band_rev[f];
+#pragma unroll
+        for (int q = 0; q < NG; ++q) {
+            const int g = 4 * q + i;
+            const bool on = g < G;
+            tb[q].qr[k] = on ? tbl[(f * 3 + 0) * G + g] : 0.f;
+            tb[q].qi[k] = on ? tbl[(f * 3 + 1) * G + g] : 0.f;
+            tb[q].cn[k] = on ? tbl[(f * 3 + 2) * G + g] : 0.f;
+            tb[q].rr[k] = tb[q].qr[k];
+            tb[q].ri[k] = tb[q].qi[k];
+        }
+    }
+    __syncthreads();
+
+    const int w0 = chunk * kFastChunk + wave * kWaveKeys;
+    const int w1 = min(w0 + kWaveKeys, N);
+    const char *kbase = (const char *)c.k;
+    const char *ph0 = (const char *)lds_phasors + b * kPhasorBlockStride;
+    const int Hq = c.n_kv_heads * G;
+    float *rw = a.raw + (((int64_t)l * c.n_seqs + s) * Hq + (int64_t)h * G) * c.max_seq_len;
+
+    double s1[NG], s2[NG];
+#pragma unroll
+    for (int q = 0; q < NG; ++q) s1[q] = s2[q] = 0.0;
+
+    int base = 0;
+    bool have_base = false;
+    const int sub = (lane >> 2) & 3;   // which of 4 consecutive steps this lane keeps for the store
+    const int row = lane >> 4;         // key of the step this lane holds after the reduction
+
+    for (int n = w0; n < w1; n += 16) {
+        float kept[NG];
+#pragma unroll
+        for (int q = 0; q < NG; ++q) kept[q] = 0.f;
+        // loads of the four steps up front: 16 B of key data and the key's position per lane
+        uint4 kd[4];
+        int pp[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int key = min(n + 4 * t + i, w1 - 1);   // past the end: repeat the last key (discarded below)
+            kd[t] = *reinterpret_cast<const uint4 *>(kbase + kv_offset(c, l, s, h, key) * 2 + b * 16);
+            pp[t] = c.pos[pos_offset(c, l, s, h, key)];
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int p = pp[t];
+            float cs[4], sn[4];
+            bool in_table = true;
+            int r = p - base;
+            if (!have_base || __builtin_amdgcn_ballot_w64((unsigned)r >= (unsigned)kPhasorRange) != 0ull) {
+                // the four positions of this step (lanes 0..3 hold one each)
+                const int p0 = __builtin_amdgcn_readlane(p, 0), p1 = __builtin_amdgcn_readlane(p, 1);
+                const int p2 = __builtin_amdgcn_readlane(p, 2), p3 = __builtin_amdgcn_readlane(p, 3);
+                const int lo = min(min(p0, p1), min(p2, p3)), hi = max(max(p0, p1), max(p2, p3));
+                if ((int64_t)hi - (int64_t)lo < kPhasorRange) {
+                    // move the base: fold e^{-i w base} into the lane's table registers
+                    base = lo;
+                    have_base = true;
+                    r = p - base;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float x = (float)__builtin_amdgcn_fract((double)base * rev[k]);
+                        const float bs = __builtin_amdgcn_sinf(x), bc = __builtin_amdgcn_cosf(x);
+#pragma unroll
+                        for (int q = 0; q < NG; ++q) {
+                            tb[q].rr[k] = tb[q].qr[k] * bc + tb[q].qi[k] * bs;
+                            tb[q].ri[k] = tb[q].qi[k] * bc - tb[q].qr[k] * bs;
+                        }
+                    }
+                } else {
+                    in_table = false;   // direct path for this step, relative to the base in force
+                }
+            }
+            if (in_table) {
+                const float4 e0 = *reinterpret_cast<const float4 *>(ph0 + r * 16);
+                const float4 e1 = *reinterpret_cast<const float4 *>(ph0 + kPhasorHalfStride + r * 16);
+                cs[0] = e0.x; sn[0] = e0.y; cs[1] = e0.z; sn[1] = e0.w;
+                cs[2] = e1.x; sn[2] = e1.y; cs[3] = e1.z; sn[3] = e1.w;
+            } else {
+                const double pd = (double)((int64_t)p - (int64_t)base);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float x = (float)__builtin_amdgcn_fract(pd * rev[k]);
+                    sn[k] = __builtin_amdgcn_sinf(x);
+                    cs[k] = __builtin_amdgcn_cosf(x);
+                }
+            }
+            float out[NG];
+            score_step<NG>(kd[t], cs, sn, tb, out);
+#pragma unroll
+            for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
+        }
+        // lane (row, sub, j) now holds key n + 4*sub + row for head j (+4q): 16 keys x 4 heads per wave
+        const int key = n + 4 * sub + row;
+        if (key < w1) {
+#pragma unroll
+            for (int q = 0; q < NG; ++q) {
+                const int g = 4 * q + i;
+                if (g < G) {
+                    rw[(int64_t)g * c.max_seq_len + key] = kept[q];
+                    const double v = (double)kept[q];
+                    s1[q] += v;
+                    s2[q] += v * v;
+                }
+            }
+        }
+    }
+
+    // per-head sums over the wave's keys: lanes with equal lane % 4 hold the same head
+#pragma unroll
+    for (int q = 0; q < NG; ++q) {
+#pragma unroll
+        for (int o = 4; o < 64; o <<= 1) {
+            s1[q] += __shfl_xor(s1[q], o, 64);
+            s2[q] += __shfl_xor(s2[q], o, 64);
+        }
+        if (lane < 4) {
+            red[wave][(4 * q + lane) * 2 + 0] = s1[q];
+            red[wave][(4 * q + lane) * 2 + 1] = s2[q];
+        }
+    }
+    __syncthreads();
+    if (tid < 2 * G) {
+        const int g = tid % G, which = tid / G;
+        double v = 0.0;
+        for (int w = 0; w < kFastWaves; ++w) v += red[w][g * 2 + which];
+        a.partials[(inst * a.n_tiles + chunk) * (2 * G) + tid] = v;
+    }
+}
+
+template <int G>
+tri_status launch_fast_g(const ScoreArgs &sa, int n_layers, hipStream_t st)
+{
+    auto kern = score_mfma_kernel<G>;
+    if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kPhasorBytes) != hipSuccess)
+        return hip_status("hipFuncSetAttribute(score_mfma_kernel)");
+    dim3 grid(sa.n_tiles, sa.c.n_seqs * sa.c.n_kv_heads, n_layers);
+    hipLaunchKernelGGL(kern, grid, dim3(kFastThreads), kPhasorBytes, st, sa);
+    return hip_status("score_mfma_kernel");
+}
+
+}  // namespace
+
+tri_status launch_phasor_table(double theta, uint4 *phasors, hipStream_t st)
+{
+    hipLaunchKernelGGL(phasor_table_kernel, dim3(2 * 16 * kPhasorRange / 256), dim3(256), 0, st, theta,
+                       reinterpret_cast<float4 *>(phasors));
+    return hip_status("phasor_table_kernel");
+}
+
+tri_status launch_score_fast(int G, const ScoreArgs &sa, int n_layers, hipStream_t st)
+{
+    switch (G) {
+        case 1: return launch_fast_g<1>(sa, n_layers, st);
+        case 2: return launch_fast_g<2>(sa, n_layers, st);
+        case 4: return launch_fast_g<4>(sa, n_layers, st);
+        case 8: return launch_fast_g<8>(sa, n_layers, st);
+    }
+    set_error("group size %d not built (1, 2, 4, 8)", G);
+    return TRI_ERR_UNSUPPORTED;
+}
+
+}  // namespace tri

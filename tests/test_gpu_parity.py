@@ -10,18 +10,21 @@ import tri_harness as H
 pytestmark = pytest.mark.gpu
 
 
-def oracle_instance(oracle, cfg, w, stats, l, s, h, threads=8):
+def oracle_instance(oracle, cfg, w, stats, l, s, h, threads=8, pairs=0):
     G = cfg.group
     n = int(w["seq_len"][s])
     return oracle.head_instance(stats[l, h * G:(h + 1) * G], w["k"][l, s, h, :n], w["pos"][l, s, h, :n],
-                                int(w["cur_pos"][s]), cfg.rope_theta, cfg.offsets, cfg.budget, threads=threads)
+                                int(w["cur_pos"][s]), cfg.rope_theta, cfg.offsets, cfg.budget, pairs=pairs,
+                                threads=threads)
 
 
-def run_and_check(oracle, cfg, instances=None, paged=False, inplace=False):
+def run_and_check(oracle, cfg, instances=None, paged=False, inplace=False, pairs=0, mutate=None):
     w = recipe.generate(cfg)
-    run = H.GpuRun(cfg, w, paged=paged)
+    if mutate is not None:
+        mutate(w)
+    run = H.GpuRun(cfg, w, paged=paged, pairs=pairs)
     stats_gpu = run.build_centers()
-    stats = oracle.centers(w["q_samples"])
+    stats = oracle.centers(w["q_samples"], pairs=pairs)
     np.testing.assert_allclose(stats_gpu, stats, rtol=3e-7, atol=1e-30)
     # score with the oracle's table so that the two sides read identical bytes
     run.centers.copy_(torch.from_numpy(stats))
@@ -37,7 +40,7 @@ def run_and_check(oracle, cfg, instances=None, paged=False, inplace=False):
         if n == 0:
             assert cnt[l, s, h] == 0
             continue
-        ref = oracle_instance(oracle, cfg, w, stats, l, s, h)
+        ref = oracle_instance(oracle, cfg, w, stats, l, s, h, pairs=pairs)
         worst_raw = max(worst_raw, H.check_raw(raw[l, s, h * G:(h + 1) * G, :n], ref["raw"]))
         worst_final = max(worst_final, H.check_final(final[l, s, h, :n], ref["final"]))
         exact += H.check_kept(idx[l, s, h], int(cnt[l, s, h]), ref["final"], ref["idx"], n, cfg.budget)
@@ -106,3 +109,35 @@ def test_group_of_eight(oracle):
     cfg = recipe.scaled(recipe.CONFIGS["c5_long"], n_layers=1, n_seqs=1, n_q_heads=16, n_kv_heads=2, seq_len=600,
                         budget=100, n_calib=128)
     run_and_check(oracle, cfg)
+
+
+def test_wild_positions(oracle):
+    """Positions that defeat the relative-position table: unsorted, gaps of up to 2^28, one sequence
+    with long runs of equal positions.  Exercises the direct path and the base moves of the MFMA kernel."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=3, n_q_heads=8, n_kv_heads=2, seq_len=700,
+                        budget=100, n_calib=128)
+
+    def mutate(w):
+        rng = np.random.default_rng(5)
+        n = cfg.seq_len
+        w["pos"][:, 0] = rng.integers(0, 1 << 28, size=(1, 2, n)).astype(np.int32)             # unsorted, huge
+        mixed = np.sort(rng.integers(0, 5000, size=(1, 2, n)), axis=-1)
+        mixed[..., 300:] += 1 << 20                                                              # one big jump
+        w["pos"][:, 1] = mixed.astype(np.int32)
+        w["pos"][:, 2] = (np.arange(n) // 37 * 3).astype(np.int32)                              # repeated positions
+        w["cur_pos"][:] = np.array([1 << 28, (1 << 20) + 5000, 100], dtype=np.int32)
+
+    run_and_check(oracle, cfg, mutate=mutate)
+
+
+def test_half_split_pairs(oracle):
+    """Band f = (x[f], x[f + d/2]): the same workload with every head vector permuted to that layout."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=1, n_q_heads=8, n_kv_heads=2, seq_len=500,
+                        budget=64, n_calib=128)
+
+    def mutate(w):
+        for name in ("k", "q_samples"):
+            x = w[name]
+            w[name] = np.ascontiguousarray(np.concatenate([x[..., 0::2], x[..., 1::2]], axis=-1))
+
+    run_and_check(oracle, cfg, pairs=1, mutate=mutate)
