@@ -14,6 +14,8 @@
 // bands); e^{-i w base} is folded into the lane's table registers whenever the wave moves its base.
 // A step whose four keys span R positions or more takes the direct path instead (phase in double,
 // v_sin_f32 / v_cos_f32), so any position layout is handled.
+#include <type_traits>
+
 #include "tri_score_common.h"
 
 namespace tri {
@@ -105,7 +107,7 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
 }
 
 // grid (ceil(Nmax / kFastChunk), S*Hkv, L), block 512.  Each wave walks kWaveKeys contiguous keys.
-template <int G>
+template <int G, bool PAGED>
 __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 {
     constexpr int NG = (G + 3) / 4;
@@ -160,71 +162,123 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     const int sub = (lane >> 2) & 3;   // which of 4 consecutive steps this lane keeps for the store
     const int row = lane >> 4;         // key of the step this lane holds after the reduction
 
-    for (int n = w0; n < w1; n += 16) {
-        float kept[NG];
-#pragma unroll
-        for (int q = 0; q < NG; ++q) kept[q] = 0.f;
-        // loads of the four steps up front: 16 B of key data and the key's position per lane
-        uint4 kd[4];
-        int pp[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int key = min(n + 4 * t + i, w1 - 1);   // past the end: repeat the last key (discarded below)
-            kd[t] = *reinterpret_cast<const uint4 *>(kbase + kv_offset(c, l, s, h, key) * 2 + b * 16);
-            pp[t] = c.pos[pos_offset(c, l, s, h, key)];
-        }
+    // Addresses: one 16-byte piece of a key row and the key's position per lane and step.
+    const int64_t head_k = ((int64_t)l * c.stride_layer + (int64_t)h * c.stride_head) * 2 + b * 16;
+    const int64_t head_p = (int64_t)l * c.pos_stride_layer + (int64_t)h * c.pos_stride_head;
+    const char *krow = kbase + head_k + (PAGED ? 0 : (int64_t)s * c.stride_sb * 2);
+    const int32_t *prow = c.pos + head_p + (PAGED ? 0 : (int64_t)s * c.pos_stride_sb);
+    const int64_t slot_bytes = c.stride_slot * 2;
+    const int32_t *bt = PAGED ? c.block_table + (int64_t)s * c.max_blocks : nullptr;
+    const int bmask = PAGED ? (1 << c.block_shift) - 1 : 0;
+
+    auto load_group = [&](int n, uint4(&kd)[4], int(&pp)[4]) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int p = pp[t];
-            float cs[4], sn[4];
-            bool in_table = true;
-            int r = p - base;
-            if (!have_base || __builtin_amdgcn_ballot_w64((unsigned)r >= (unsigned)kPhasorRange) != 0ull) {
-                // the four positions of this step (lanes 0..3 hold one each)
-                const int p0 = __builtin_amdgcn_readlane(p, 0), p1 = __builtin_amdgcn_readlane(p, 1);
-                const int p2 = __builtin_amdgcn_readlane(p, 2), p3 = __builtin_amdgcn_readlane(p, 3);
-                const int lo = min(min(p0, p1), min(p2, p3)), hi = max(max(p0, p1), max(p2, p3));
-                if ((int64_t)hi - (int64_t)lo < kPhasorRange) {
-                    // move the base: fold e^{-i w base} into the lane's table registers
-                    base = lo;
-                    have_base = true;
-                    r = p - base;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const float x = (float)__builtin_amdgcn_fract((double)base * rev[k]);
-                        const float bs = __builtin_amdgcn_sinf(x), bc = __builtin_amdgcn_cosf(x);
-#pragma unroll
-                        for (int q = 0; q < NG; ++q) {
-                            tb[q].rr[k] = tb[q].qr[k] * bc + tb[q].qi[k] * bs;
-                            tb[q].ri[k] = tb[q].qi[k] * bc - tb[q].qr[k] * bs;
-                        }
-                    }
-                } else {
-                    in_table = false;   // direct path for this step, relative to the base in force
-                }
+            const int key = min(n + 4 * t + i, w1 - 1);   // past the end: repeat the last key (discarded later)
+            if constexpr (PAGED) {
+                const int blk = bt[key >> c.block_shift];
+                const int slot = key & bmask;
+                kd[t] = *reinterpret_cast<const uint4 *>(krow + (int64_t)blk * c.stride_sb * 2 + slot * slot_bytes);
+                pp[t] = prow[(int64_t)blk * c.pos_stride_sb + slot];
+            } else {
+                kd[t] = *reinterpret_cast<const uint4 *>(krow + key * slot_bytes);
+                pp[t] = prow[key];
             }
-            if (in_table) {
-                const float4 e0 = *reinterpret_cast<const float4 *>(ph0 + r * 16);
-                const float4 e1 = *reinterpret_cast<const float4 *>(ph0 + kPhasorHalfStride + r * 16);
-                cs[0] = e0.x; sn[0] = e0.y; cs[1] = e0.z; sn[1] = e0.w;
-                cs[2] = e1.x; sn[2] = e1.y; cs[3] = e1.z; sn[3] = e1.w;
+        }
+    };
+
+    // fold e^{-i w base} into the lane's table registers
+    auto move_base = [&](int new_base) {
+        base = new_base;
+        have_base = true;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float x = (float)__builtin_amdgcn_fract((double)base * rev[k]);
+            const float bs = __builtin_amdgcn_sinf(x), bc = __builtin_amdgcn_cosf(x);
+#pragma unroll
+            for (int q = 0; q < NG; ++q) {
+                tb[q].rr[k] = tb[q].qr[k] * bc + tb[q].qi[k] * bs;
+                tb[q].ri[k] = tb[q].qi[k] * bc - tb[q].qr[k] * bs;
+            }
+        }
+    };
+
+    // one step with the key's phasors read from the table (0 <= r < R)
+    auto step_table = [&](const uint4 &kd, int r, float(&out)[NG]) {
+        const float4 e0 = *reinterpret_cast<const float4 *>(ph0 + r * 16);
+        const float4 e1 = *reinterpret_cast<const float4 *>(ph0 + kPhasorHalfStride + r * 16);
+        const float cs[4] = {e0.x, e0.z, e1.x, e1.z}, sn[4] = {e0.y, e0.w, e1.y, e1.w};
+        score_step<NG>(kd, cs, sn, tb, out);
+    };
+
+    // one step for any four positions: move the base if that brings them into the table, else
+    // evaluate the phasors directly (phase in double, relative to the base in force)
+    auto step_general = [&](const uint4 &kd, int p, float(&out)[NG]) {
+        int r = p - base;
+        if (!have_base || __builtin_amdgcn_ballot_w64((unsigned)r >= (unsigned)kPhasorRange) != 0ull) {
+            const int p0 = __builtin_amdgcn_readlane(p, 0), p1 = __builtin_amdgcn_readlane(p, 1);
+            const int p2 = __builtin_amdgcn_readlane(p, 2), p3 = __builtin_amdgcn_readlane(p, 3);
+            const int lo = min(min(p0, p1), min(p2, p3)), hi = max(max(p0, p1), max(p2, p3));
+            if ((int64_t)hi - (int64_t)lo < kPhasorRange) {
+                move_base(lo);
+                r = p - base;
             } else {
                 const double pd = (double)((int64_t)p - (int64_t)base);
+                float cs[4], sn[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const float x = (float)__builtin_amdgcn_fract(pd * rev[k]);
                     sn[k] = __builtin_amdgcn_sinf(x);
                     cs[k] = __builtin_amdgcn_cosf(x);
                 }
+                score_step<NG>(kd, cs, sn, tb, out);
+                return;
             }
-            float out[NG];
-            score_step<NG>(kd[t], cs, sn, tb, out);
+        }
+        step_table(kd, r, out);
+    };
+
+    auto process_group = [&](int n, const uint4(&kd)[4], const int(&pp)[4], auto full_tag) {
+        constexpr bool kFull = decltype(full_tag)::value;   // all 16 keys of the group exist
+        float kept[NG];
 #pragma unroll
-            for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
+        for (int q = 0; q < NG; ++q) kept[q] = 0.f;
+        // common case: all 16 positions of the group fall in the table around the current base
+        const unsigned far = max(max((unsigned)(pp[0] - base), (unsigned)(pp[1] - base)),
+                                 max((unsigned)(pp[2] - base), (unsigned)(pp[3] - base)));
+        bool fast = have_base && __builtin_amdgcn_ballot_w64(far >= (unsigned)kPhasorRange) == 0ull;
+        if (!fast) {
+            // span of the 16 positions (lanes 0..3 hold four each)
+            int lo = min(min(pp[0], pp[1]), min(pp[2], pp[3])), hi = max(max(pp[0], pp[1]), max(pp[2], pp[3]));
+            lo = min(min(__builtin_amdgcn_readlane(lo, 0), __builtin_amdgcn_readlane(lo, 1)),
+                     min(__builtin_amdgcn_readlane(lo, 2), __builtin_amdgcn_readlane(lo, 3)));
+            hi = max(max(__builtin_amdgcn_readlane(hi, 0), __builtin_amdgcn_readlane(hi, 1)),
+                     max(__builtin_amdgcn_readlane(hi, 2), __builtin_amdgcn_readlane(hi, 3)));
+            if ((int64_t)hi - (int64_t)lo < kPhasorRange) {
+                move_base(lo);
+                fast = true;
+            }
+        }
+        if (fast) {
+            float out[4][NG];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) step_table(kd[t], pp[t] - base, out[t]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[t][q] : kept[q];
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                float out[NG];
+                step_general(kd[t], pp[t], out);
+#pragma unroll
+                for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
+            }
         }
         // lane (row, sub, j) now holds key n + 4*sub + row for head j (+4q): 16 keys x 4 heads per wave
         const int key = n + 4 * sub + row;
-        if (key < w1) {
+        if (kFull || key < w1) {
 #pragma unroll
             for (int q = 0; q < NG; ++q) {
                 const int g = 4 * q + i;
@@ -235,6 +289,27 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
                     s2[q] += v * v;
                 }
             }
+        }
+    };
+
+    // Two register buffers: the loads of the next 16 keys are in flight while this group is scored.
+    // Loads are unconditional (indices are clamped to the wave's last key), so that the main loop is
+    // straight-line code and the compiler can count outstanding loads exactly.
+    uint4 kdA[4], kdB[4];
+    int ppA[4], ppB[4];
+    int n = w0;
+    if (w0 < w1) {
+        load_group(n, kdA, ppA);
+        for (; n + 32 <= w1; n += 32) {
+            load_group(n + 16, kdB, ppB);
+            process_group(n, kdA, ppA, std::true_type{});
+            load_group(n + 32, kdA, ppA);
+            process_group(n + 16, kdB, ppB, std::true_type{});
+        }
+        if (n < w1) {   // at most 31 keys left
+            load_group(n + 16, kdB, ppB);
+            process_group(n, kdA, ppA, std::false_type{});
+            if (n + 16 < w1) process_group(n + 16, kdB, ppB, std::false_type{});
         }
     }
 
@@ -263,7 +338,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 template <int G>
 tri_status launch_fast_g(const ScoreArgs &sa, int n_layers, hipStream_t st)
 {
-    auto kern = score_mfma_kernel<G>;
+    auto kern = sa.c.block_shift >= 0 ? score_mfma_kernel<G, true> : score_mfma_kernel<G, false>;
     if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kPhasorBytes) != hipSuccess)
         return hip_status("hipFuncSetAttribute(score_mfma_kernel)");
     dim3 grid(sa.n_tiles, sa.c.n_seqs * sa.c.n_kv_heads, n_layers);
