@@ -74,12 +74,14 @@ __device__ __forceinline__ float reduce_blocks(float4v acc)
     return c;
 }
 
-// The lane's slice of the folded centre table for one group of four query heads.
+// The lane's slice of the folded centre table for one group of four query heads, rotated by
+// e^{-i w base}: what the MFMAs consume.
 struct LaneTable {
-    float qr[4], qi[4];   // Re / Im of Qhat for bands 4b..4b+3 (absolute: p_q folded in, no base)
-    float rr[4], ri[4];   // the same rotated by e^{-i w base}: what the MFMAs consume
+    float rr[4], ri[4];   // Re / Im of Qhat e^{-i w base} for bands 4b..4b+3
     float cn[4];          // norm-term weight
 };
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 template <int NG>
 __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4], const float (&sn)[4],
@@ -94,7 +96,9 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
         const float re = bf16_lo(w[k]), im = bf16_hi(w[k]);
         const float kr = re * cs[k] - im * sn[k];
         const float ki = re * sn[k] + im * cs[k];
-        const float m = __builtin_amdgcn_sqrtf(re * re + im * im);
+        // |k_f|^2 straight from the packed bf16 pair (products of bf16 are exact in fp32)
+        const bf16x2 kk = __builtin_bit_cast(bf16x2, w[k]);
+        const float m = __builtin_amdgcn_sqrtf(__builtin_amdgcn_fdot2_f32_bf16(kk, kk, 0.0f, false));
 #pragma unroll
         for (int q = 0; q < NG; ++q) {
             acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(kr, tb[q].rr[k], acc[q], 0, 0, 0);
@@ -106,16 +110,20 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
     for (int q = 0; q < NG; ++q) out[q] = reduce_blocks(acc[q]);
 }
 
-// grid (ceil(Nmax / kFastChunk), S*Hkv, L), block 512.  Each wave walks kWaveKeys contiguous keys.
+// grid (ceil(Nmax / kFastChunk), S*Hkv, L), block 512.  Each wave walks kWaveKeys contiguous keys in
+// groups of 16 (4 steps).  PAGED: block_size >= 16, so a group never straddles a block.
 template <int G, bool PAGED>
 __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 {
     constexpr int NG = (G + 3) / 4;
     extern __shared__ uint4 lds_phasors[];
     __shared__ double red[kFastWaves][2 * 4 * NG];
+    __shared__ double lds_rev[kBands];          // omega_f / 2pi
+    __shared__ float lds_tab[kBands * 3 * G];   // this head-instance's folded table (no base)
 
     const CacheView &c = a.c;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps loop control scalar
     const int b = lane >> 2, i = lane & 3;
     const int chunk = blockIdx.x;
     const int s = blockIdx.y / c.n_kv_heads, h = blockIdx.y % c.n_kv_heads;
@@ -123,32 +131,26 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     const int N = c.seq_len[s];
     if (chunk * kFastChunk >= N) return;   // uniform over the workgroup
 
-    for (int k = tid; k < kPhasorBytes / 16; k += kFastThreads) lds_phasors[k] = a.phasors[k];
-
     const int64_t inst = ((int64_t)l * c.n_seqs + s) * c.n_kv_heads + h;
-    const float *tbl = a.table + inst * (kBands * 3 * G);
+    for (int k = tid; k < kPhasorBytes / 16; k += kFastThreads) lds_phasors[k] = a.phasors[k];
+    for (int k = tid; k < kBands * 3 * G; k += kFastThreads) lds_tab[k] = a.table[inst * (kBands * 3 * G) + k];
+    if (tid < kBands) lds_rev[tid] = a.band_rev[tid];
+    __syncthreads();
+
     LaneTable tb[NG];
-    double rev[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int f = 4 * b + k;
-        rev[k] = a.band_rev[f];
+    for (int k = 0; k < 4; ++k)
 #pragma unroll
         for (int q = 0; q < NG; ++q) {
-            const int g = 4 * q + i;
+            const int f = 4 * b + k, g = 4 * q + i;
             const bool on = g < G;
-            tb[q].qr[k] = on ? tbl[(f * 3 + 0) * G + g] : 0.f;
-            tb[q].qi[k] = on ? tbl[(f * 3 + 1) * G + g] : 0.f;
-            tb[q].cn[k] = on ? tbl[(f * 3 + 2) * G + g] : 0.f;
-            tb[q].rr[k] = tb[q].qr[k];
-            tb[q].ri[k] = tb[q].qi[k];
+            tb[q].rr[k] = on ? lds_tab[(f * 3 + 0) * G + g] : 0.f;
+            tb[q].ri[k] = on ? lds_tab[(f * 3 + 1) * G + g] : 0.f;
+            tb[q].cn[k] = on ? lds_tab[(f * 3 + 2) * G + g] : 0.f;
         }
-    }
-    __syncthreads();
 
     const int w0 = chunk * kFastChunk + wave * kWaveKeys;
     const int w1 = min(w0 + kWaveKeys, N);
-    const char *kbase = (const char *)c.k;
     const char *ph0 = (const char *)lds_phasors + b * kPhasorBlockStride;
     const int Hq = c.n_kv_heads * G;
     float *rw = a.raw + (((int64_t)l * c.n_seqs + s) * Hq + (int64_t)h * G) * c.max_seq_len;
@@ -157,48 +159,92 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 #pragma unroll
     for (int q = 0; q < NG; ++q) s1[q] = s2[q] = 0.0;
 
-    int base = 0;
-    bool have_base = false;
+    int base = 0;                      // base = 0 with the unrotated table is a valid state
     const int sub = (lane >> 2) & 3;   // which of 4 consecutive steps this lane keeps for the store
     const int row = lane >> 4;         // key of the step this lane holds after the reduction
 
-    // Addresses: one 16-byte piece of a key row and the key's position per lane and step.
-    const int64_t head_k = ((int64_t)l * c.stride_layer + (int64_t)h * c.stride_head) * 2 + b * 16;
-    const int64_t head_p = (int64_t)l * c.pos_stride_layer + (int64_t)h * c.pos_stride_head;
-    const char *krow = kbase + head_k + (PAGED ? 0 : (int64_t)s * c.stride_sb * 2);
-    const int32_t *prow = c.pos + head_p + (PAGED ? 0 : (int64_t)s * c.pos_stride_sb);
-    const int64_t slot_bytes = c.stride_slot * 2;
+    // Addresses.  Everything that depends on the group is wave-uniform (scalar registers); a lane
+    // adds its own constant offset: key (4t + i) of the group, 16-byte piece b of the row.
+    const uint32_t slot_bytes = (uint32_t)c.stride_slot * 2u;
+    const char *krow = (const char *)c.k + ((int64_t)l * c.stride_layer + (int64_t)h * c.stride_head) * 2 +
+                       (PAGED ? 0 : (int64_t)s * c.stride_sb * 2);
+    const int32_t *prow = c.pos + (int64_t)l * c.pos_stride_layer + (int64_t)h * c.pos_stride_head +
+                          (PAGED ? 0 : (int64_t)s * c.pos_stride_sb);
     const int32_t *bt = PAGED ? c.block_table + (int64_t)s * c.max_blocks : nullptr;
     const int bmask = PAGED ? (1 << c.block_shift) - 1 : 0;
+    // Loads are issued in the coalesced lane order (lane = 16*key + piece: a wave instruction reads
+    // four whole 256-byte rows front to back) and handed to the consumer lane (b, i) = piece b of
+    // key i with one cross-lane permute per dword.  Loading straight in consumer order costs the
+    // texture-address unit four cache-line lookups per lane quad and makes it the bottleneck.
+    const int ld_key = lane >> 4, ld_piece = lane & 15;
+    uint32_t koff[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) koff[t] = (uint32_t)(4 * t + ld_key) * slot_bytes + (uint32_t)ld_piece * 16u;
+    const int perm_k = (16 * i + b) * 4;   // ds_bpermute address: source lane of this lane's K piece
+    const int perm_p = i * 4;              // source lane (4t + i) of this lane's position at step t, plus 16*t
 
-    auto load_group = [&](int n, uint4(&kd)[4], int(&pp)[4]) {
+    // group starting at key n (a multiple of 16): uniform base pointers of its K rows and positions
+    auto group_ptrs = [&](int n, const char *&kp, const int32_t *&pq) {
+        if constexpr (PAGED) {
+            const int blk = __builtin_amdgcn_readfirstlane(bt[n >> c.block_shift]);
+            const int slot = n & bmask;
+            kp = krow + (int64_t)blk * c.stride_sb * 2 + (int64_t)slot * slot_bytes;
+            pq = prow + (int64_t)blk * c.pos_stride_sb + slot;
+        } else {
+            kp = krow + (int64_t)n * slot_bytes;
+            pq = prow + n;
+        }
+    };
+
+    // all 16 keys of the group exist: no per-lane address arithmetic at all.  kd[t] = rows 4t..4t+3 in
+    // load order, pp = the 16 positions (lane l holds key l % 16).
+    auto load_full = [&](int n, uint4(&kd)[4], int &pp) {
+        const char *kp;
+        const int32_t *pq;
+        group_ptrs(n, kp, pq);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) kd[t] = *reinterpret_cast<const uint4 *>(kp + koff[t]);
+        pp = pq[ld_piece];
+    };
+
+    // last, partial group: keys past the end repeat the last one (their results are discarded)
+    auto load_tail = [&](int n, int cnt, uint4(&kd)[4], int &pp) {
+        const char *kp;
+        const int32_t *pq;
+        group_ptrs(n, kp, pq);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int key = min(n + 4 * t + i, w1 - 1);   // past the end: repeat the last key (discarded later)
-            if constexpr (PAGED) {
-                const int blk = bt[key >> c.block_shift];
-                const int slot = key & bmask;
-                kd[t] = *reinterpret_cast<const uint4 *>(krow + (int64_t)blk * c.stride_sb * 2 + slot * slot_bytes);
-                pp[t] = prow[(int64_t)blk * c.pos_stride_sb + slot];
-            } else {
-                kd[t] = *reinterpret_cast<const uint4 *>(krow + key * slot_bytes);
-                pp[t] = prow[key];
-            }
+            const int j = min(4 * t + ld_key, cnt - 1);
+            kd[t] = *reinterpret_cast<const uint4 *>(kp + (uint32_t)j * slot_bytes + (uint32_t)ld_piece * 16u);
         }
+        pp = pq[min(ld_piece, cnt - 1)];
+    };
+
+    // load order -> consumer order
+    auto to_consumer = [&](const uint4 &raw) {
+        uint4 v;
+        v.x = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.x);
+        v.y = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.y);
+        v.z = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.z);
+        v.w = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.w);
+        return v;
     };
 
     // fold e^{-i w base} into the lane's table registers
     auto move_base = [&](int new_base) {
         base = new_base;
-        have_base = true;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float x = (float)__builtin_amdgcn_fract((double)base * rev[k]);
+            const int f = 4 * b + k;
+            const float x = (float)__builtin_amdgcn_fract((double)base * lds_rev[f]);
             const float bs = __builtin_amdgcn_sinf(x), bc = __builtin_amdgcn_cosf(x);
 #pragma unroll
             for (int q = 0; q < NG; ++q) {
-                tb[q].rr[k] = tb[q].qr[k] * bc + tb[q].qi[k] * bs;
-                tb[q].ri[k] = tb[q].qi[k] * bc - tb[q].qr[k] * bs;
+                const int g = 4 * q + i;
+                const float qr = g < G ? lds_tab[(f * 3 + 0) * G + g] : 0.f;
+                const float qi = g < G ? lds_tab[(f * 3 + 1) * G + g] : 0.f;
+                tb[q].rr[k] = qr * bc + qi * bs;
+                tb[q].ri[k] = qi * bc - qr * bs;
             }
         }
     };
@@ -215,7 +261,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     // evaluate the phasors directly (phase in double, relative to the base in force)
     auto step_general = [&](const uint4 &kd, int p, float(&out)[NG]) {
         int r = p - base;
-        if (!have_base || __builtin_amdgcn_ballot_w64((unsigned)r >= (unsigned)kPhasorRange) != 0ull) {
+        if (__builtin_amdgcn_ballot_w64((unsigned)r >= (unsigned)kPhasorRange) != 0ull) {
             const int p0 = __builtin_amdgcn_readlane(p, 0), p1 = __builtin_amdgcn_readlane(p, 1);
             const int p2 = __builtin_amdgcn_readlane(p, 2), p3 = __builtin_amdgcn_readlane(p, 3);
             const int lo = min(min(p0, p1), min(p2, p3)), hi = max(max(p0, p1), max(p2, p3));
@@ -227,7 +273,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
                 float cs[4], sn[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    const float x = (float)__builtin_amdgcn_fract(pd * rev[k]);
+                    const float x = (float)__builtin_amdgcn_fract(pd * lds_rev[4 * b + k]);
                     sn[k] = __builtin_amdgcn_sinf(x);
                     cs[k] = __builtin_amdgcn_cosf(x);
                 }
@@ -238,15 +284,22 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
         step_table(kd, r, out);
     };
 
-    auto process_group = [&](int n, const uint4(&kd)[4], const int(&pp)[4], auto full_tag) {
+    auto process_group = [&](int n, const uint4(&kraw)[4], int praw, auto full_tag) {
         constexpr bool kFull = decltype(full_tag)::value;   // all 16 keys of the group exist
+        uint4 kd[4];
+        int pp[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            kd[t] = to_consumer(kraw[t]);
+            pp[t] = __builtin_amdgcn_ds_bpermute(perm_p + 16 * t, praw);
+        }
         float kept[NG];
 #pragma unroll
         for (int q = 0; q < NG; ++q) kept[q] = 0.f;
         // common case: all 16 positions of the group fall in the table around the current base
         const unsigned far = max(max((unsigned)(pp[0] - base), (unsigned)(pp[1] - base)),
                                  max((unsigned)(pp[2] - base), (unsigned)(pp[3] - base)));
-        bool fast = have_base && __builtin_amdgcn_ballot_w64(far >= (unsigned)kPhasorRange) == 0ull;
+        bool fast = __builtin_amdgcn_ballot_w64(far >= (unsigned)kPhasorRange) == 0ull;
         if (!fast) {
             // span of the 16 positions (lanes 0..3 hold four each)
             int lo = min(min(pp[0], pp[1]), min(pp[2], pp[3])), hi = max(max(pp[0], pp[1]), max(pp[2], pp[3]));
@@ -292,24 +345,29 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
         }
     };
 
-    // Two register buffers: the loads of the next 16 keys are in flight while this group is scored.
-    // Loads are unconditional (indices are clamped to the wave's last key), so that the main loop is
-    // straight-line code and the compiler can count outstanding loads exactly.
-    uint4 kdA[4], kdB[4];
-    int ppA[4], ppB[4];
-    int n = w0;
+    // Two register buffers: the loads of the next group are in flight while one is scored.  Inside the
+    // main loop every load is unconditional (a group index past the last full group is clamped to it
+    // and its data ignored), so the loop is straight-line code and the compiler can count
+    // outstanding loads exactly.
+    const int n_full = (w1 - w0) >> 4, rem = (w1 - w0) & 15;
     if (w0 < w1) {
-        load_group(n, kdA, ppA);
-        for (; n + 32 <= w1; n += 32) {
-            load_group(n + 16, kdB, ppB);
-            process_group(n, kdA, ppA, std::true_type{});
-            load_group(n + 32, kdA, ppA);
-            process_group(n + 16, kdB, ppB, std::true_type{});
+        uint4 kdA[4], kdB[4];
+        int ppA, ppB;
+        int g = 0;
+        if (n_full > 0) {
+            const int last = n_full - 1;
+            load_full(w0, kdA, ppA);
+            for (; g + 2 <= n_full; g += 2) {
+                load_full(w0 + 16 * (g + 1), kdB, ppB);
+                process_group(w0 + 16 * g, kdA, ppA, std::true_type{});
+                load_full(w0 + 16 * min(g + 2, last), kdA, ppA);
+                process_group(w0 + 16 * (g + 1), kdB, ppB, std::true_type{});
+            }
+            if (g < n_full) process_group(w0 + 16 * g, kdA, ppA, std::true_type{});
         }
-        if (n < w1) {   // at most 31 keys left
-            load_group(n + 16, kdB, ppB);
-            process_group(n, kdA, ppA, std::false_type{});
-            if (n + 16 < w1) process_group(n + 16, kdB, ppB, std::false_type{});
+        if (rem) {
+            load_tail(w0 + 16 * n_full, rem, kdB, ppB);
+            process_group(w0 + 16 * n_full, kdB, ppB, std::false_type{});
         }
     }
 
