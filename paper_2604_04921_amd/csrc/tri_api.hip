@@ -260,7 +260,8 @@ tri_status tri_select_topk(const tri_model *model, const float *final_scores, co
         set_error("tri_select_topk: final_scores, kept_idx, kept_cnt and budget >= 1 required");
         return TRI_ERR_INVALID_ARG;
     }
-    return launch_select(*model, final_scores, *cache, budget, kept_idx, kept_cnt, (hipStream_t)stream);
+    return launch_select(*model, final_scores, nullptr, nullptr, nullptr, *cache, budget, kept_idx, kept_cnt,
+                         (hipStream_t)stream);
 }
 
 tri_status tri_compact(const tri_model *model, const tri_cache *src, const tri_cache *dst, int32_t budget,
@@ -305,9 +306,13 @@ tri_status tri_compress_step(const tri_model *model, const float *centers, const
     const Workspace wl = workspace_layout(*model, *src, budget);
     if ((rc = check_workspace(wl, workspace, ws_bytes)) != TRI_OK) return rc;
     char *ws = (char *)workspace;
-    float *fin = reinterpret_cast<float *>(ws + wl.final_);
-    if ((rc = launch_score(*model, centers, *src, fin, nullptr, ws, wl, (hipStream_t)stream)) != TRI_OK) return rc;
-    if ((rc = launch_select(*model, fin, *src, budget, kept_idx, kept_cnt, (hipStream_t)stream)) != TRI_OK) return rc;
+    // raw scores and their statistics stay in the workspace; the selection forms the final scores itself
+    if ((rc = launch_score(*model, centers, *src, nullptr, nullptr, ws, wl, (hipStream_t)stream)) != TRI_OK) return rc;
+    if ((rc = launch_select(*model, nullptr, reinterpret_cast<const float *>(ws + wl.raw),
+                            reinterpret_cast<const double *>(ws + wl.stats),
+                            reinterpret_cast<uint32_t *>(ws + wl.final_), *src, budget, kept_idx, kept_cnt,
+                            (hipStream_t)stream)) != TRI_OK)
+        return rc;
     return tri_compact(model, src, dst, budget, kept_idx, kept_cnt, new_seq_len, stream);
 }
 

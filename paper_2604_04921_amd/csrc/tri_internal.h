@@ -75,8 +75,10 @@ tri_status launch_centers(const tri_model &m, const void *q, int32_t q_dtype, in
                           float *out, hipStream_t st);
 tri_status launch_score(const tri_model &m, const float *centers, const tri_cache &c, float *final_out,
                         float *raw_out, char *ws, const Workspace &wl, hipStream_t st);
-tri_status launch_select(const tri_model &m, const float *final_scores, const tri_cache &c, int32_t budget,
-                         int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st);
+// final_scores given: select on them; else form them from raw + stats (scratch: keys of long sequences)
+tri_status launch_select(const tri_model &m, const float *final_scores, const float *raw, const double *stats,
+                         uint32_t *scratch, const tri_cache &c, int32_t budget, int32_t *kept_idx,
+                         int32_t *kept_cnt, hipStream_t st);
 tri_status launch_compact(const tri_model &m, const tri_cache &src, const tri_cache &dst, int32_t budget,
                           const int32_t *kept_idx, const int32_t *kept_cnt, int32_t *new_seq_len,
                           hipStream_t st);
