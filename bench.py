@@ -19,9 +19,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 SCORE_BYTES_PER_KEY = 260      # one bf16 K row (2*128 B) + one int32 position, read once
 STEP_BYTES = lambda n, b: 260 * n + 1032 * min(n, b)   # + survivors' K, V, pos read and written
 
-# HBM traffic of one score-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, scaled by
-# a copy kernel of known size); see profiles/.  None until measured for that workload.
-MEASURED_TRAFFIC = {}
+# HBM bytes of one score-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE in two runs,
+# each scaled by what the same counter reads for a plain device copy of known size: FETCH_SIZE reads 0.5 of the
+# bytes a 256 MiB copy fetches, WRITE_SIZE 1.0); summary in profiles/pmc_traffic_c3_model.md.
+MEASURED_TRAFFIC = {"c3_model/dense": 39.42e9 + 2.66e9}
 
 
 def main():
@@ -35,6 +36,8 @@ def main():
     ap.add_argument("--cpu-instances", type=int, default=4, help="head-instances the CPU oracle is timed on")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--split", action="store_true", help="call the three entry points instead of the fused one")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
@@ -70,6 +73,11 @@ def main():
     new_len = torch.empty((S,), dtype=torch.int32, device=dev)
     ws = torch.empty(T.tri_workspace_size(model, src, B), dtype=torch.uint8, device=dev)
     final = torch.empty((L, S, Hkv, cfg.seq_len), dtype=torch.float32, device=dev) if args.split else None
+    if args.copy_calibration:   # reads 2^30 bytes and writes 2^30 bytes
+        a_ = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b_ = torch.empty_like(a_)
+        b_.copy_(a_)
+        del a_, b_
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
 
