@@ -38,7 +38,14 @@ def main():
     ap.add_argument("--split", action="store_true", help="call the three entry points instead of the fused one")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic for scaling rocprofv3 byte counters)")
+    ap.add_argument("--hbm-probe", action="store_true",
+                    help="instead of the benchmark, print what a plain streaming read reaches on this GPU, alone "
+                         "and with a thin write stream mixed in")
     args = ap.parse_args()
+    if args.hbm_probe:
+        from workload import device
+        print(json.dumps({"hbm_probe_GBps": device.hbm_probe(), "peak_GBps": HBM_PEAK_GBS}), flush=True)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
