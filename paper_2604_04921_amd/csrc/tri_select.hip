@@ -179,9 +179,242 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
     }
 }
 
+// Register-resident variant for sequences of at most 1024 * KPT keys: every thread keeps KPT keys
+// (slot n = j * 1024 + tid) in registers.
+//   1. One histogram pass over 2048 *linear* bins of the score on [-4, 12) (monotone in the score, so
+//      a valid coarse partition; z-scores spread over hundreds of bins, whereas the top bits of their
+//      float image share a handful of values and would serialise the LDS atomics).
+//   2. The bin holding the B-th largest score is found with one scan; its few keys are gathered in LDS
+//      and ranked exactly (key descending, slot ascending), which gives the threshold key and the number
+//      of threshold ties to keep.  A bin with more keys than the LDS list holds (many equal scores)
+//      is resolved one bit at a time from the registers instead.
+//   3. Ordered emit with three barriers: per-(row, wave) counts from ballots, one scan, the stores.
+constexpr int kSelCand = 2048;   // keys of the threshold bin ranked in LDS
+
+__device__ __forceinline__ float key_to_float(uint32_t u)
+{
+    return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
+}
+__device__ __forceinline__ int linear_bin(uint32_t u)
+{
+    const float x = (key_to_float(u) + 4.0f) * 128.0f;   // 2048 bins over [-4, 12)
+    return (int)fminf(fmaxf(x, 0.0f), 2047.0f);
+}
+
+template <int G, int KPT>
+__global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
+{
+    __shared__ uint32_t hist[kSelBins];
+    __shared__ uint32_t cand_key[kSelCand];
+    __shared__ int32_t cand_idx[kSelCand];
+    __shared__ uint32_t row_g[KPT * kSelWaves], row_e[KPT * kSelWaves];   // [row j][wave], then exclusive prefixes
+    __shared__ uint32_t scan_tot[2][kSelWaves];
+    __shared__ uint32_t sh[36];   // 0: selected bin, 1: need inside it, 2: candidate count, 3: threshold key, 4..35: bit counters / tie count
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int inst = blockIdx.x;
+    const int s = (inst / a.n_kv_heads) % a.n_seqs;
+    const int N = a.seq_len[s];
+    const int B = a.budget;
+    int32_t *out = a.kept_idx + (int64_t)inst * B;
+    if (tid == 0) a.kept_cnt[inst] = N < B ? N : B;
+    if (N <= B) {  // nothing to evict: keep every slot
+        for (int n = tid; n < N; n += kSelThreads) out[n] = n;
+        return;
+    }
+    for (int k = tid; k < kSelBins; k += kSelThreads) hist[k] = 0u;
+    if (tid < 36) sh[tid] = 0u;
+    __syncthreads();
+
+    // ---- keys into registers, histogram of their linear bins
+    uint32_t key[KPT];
+    {
+        const float *rw = G > 0 ? a.raw + (int64_t)inst * (G > 0 ? G : 1) * a.max_seq_len : nullptr;
+        const float *fs = G == 0 ? a.final_ + (int64_t)inst * a.max_seq_len : nullptr;
+        double mu[G > 0 ? G : 1], rs[G > 0 ? G : 1];
+        if constexpr (G > 0) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                mu[g] = a.stats[((int64_t)inst * G + g) * 2];
+                rs[g] = a.stats[((int64_t)inst * G + g) * 2 + 1];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const int n = j * kSelThreads + tid;
+            key[j] = 0u;
+            if (n < N) {
+                float f;
+                if constexpr (G > 0) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const float z = (float)(((double)rw[(int64_t)g * a.max_seq_len + n] - mu[g]) * rs[g]);
+                        f = g == 0 ? z : fmaxf(f, z);
+                    }
+                } else {
+                    f = fs[n];
+                }
+                key[j] = order_key(f);
+                atomicAdd(&hist[linear_bin(key[j])], 1u);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- the bin holding the B-th largest: thread t owns bins 2047-2t and 2046-2t
+    {
+        const uint32_t v0 = hist[kSelBins - 1 - 2 * tid], v1 = hist[kSelBins - 2 - 2 * tid];
+        uint32_t cum = v0 + v1;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t t = __shfl_up(cum, o, 64);
+            if (lane >= o) cum += t;
+        }
+        if (lane == 63) scan_tot[0][wave] = cum;
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) cum += scan_tot[0][w];
+        const uint32_t excl = cum - v0 - v1, need = (uint32_t)B;
+        if (excl < need && need <= excl + v0) {
+            sh[0] = (uint32_t)(kSelBins - 1 - 2 * tid);
+            sh[1] = need - excl;
+        } else if (excl + v0 < need && need <= cum) {
+            sh[0] = (uint32_t)(kSelBins - 2 - 2 * tid);
+            sh[1] = need - excl - v0;
+        }
+    }
+    __syncthreads();
+    const int sel_bin = (int)sh[0];
+    uint32_t need = sh[1];   // how many keys of the selected bin are kept (>= 1)
+
+    // ---- gather the selected bin's keys (any order; ranks below do not depend on it)
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int n = j * kSelThreads + tid;
+        const bool hit = n < N && linear_bin(key[j]) == sel_bin;
+        const uint64_t hm = __ballot(hit);
+        if (hm) {
+            uint32_t base = 0u;
+            if (lane == 0) base = atomicAdd(&sh[2], (uint32_t)__popcll(hm));
+            base = __builtin_amdgcn_readfirstlane(base);
+            const uint32_t pos = base + (uint32_t)__popcll(hm & ((1ull << lane) - 1ull));
+            if (hit && pos < (uint32_t)kSelCand) {
+                cand_key[pos] = key[j];
+                cand_idx[pos] = n;
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t m = sh[2];
+    uint32_t thr;
+    if (m <= (uint32_t)kSelCand) {
+        // exact rank of every candidate among the candidates: key descending, slot ascending
+        for (uint32_t c = tid; c < m; c += kSelThreads) {
+            const uint32_t kc = cand_key[c];
+            const int32_t ic = cand_idx[c];
+            uint32_t rank = 0u;
+            for (uint32_t o = 0; o < m; ++o) {
+                const uint32_t ko = cand_key[o];
+                rank += (ko > kc || (ko == kc && cand_idx[o] < ic)) ? 1u : 0u;
+            }
+            if (rank == need - 1u) sh[3] = kc;   // the last kept candidate defines the threshold
+        }
+        __syncthreads();
+        thr = sh[3];
+        // threshold ties kept = need - (candidates strictly above the threshold)
+        uint32_t above = 0u;
+        for (uint32_t c = tid; c < m; c += kSelThreads) above += cand_key[c] > thr ? 1u : 0u;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) above += __shfl_xor(above, o, 64);
+        if (lane == 0 && above) atomicAdd(&sh[4], above);
+        __syncthreads();
+        need -= sh[4];
+    } else {
+        // too many keys in one bin (many equal scores): one bit at a time, keys of the bin only
+        uint32_t prefix = 0u, mask = 0u;
+#pragma unroll 1
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t bm = 1u << bit;
+            uint32_t c = 0u;
+#pragma unroll
+            for (int j = 0; j < KPT; ++j) {
+                const bool in = j * kSelThreads + tid < N && linear_bin(key[j]) == sel_bin;
+                c += (uint32_t)__popcll(__ballot(in && (key[j] & mask) == prefix && (key[j] & bm) != 0u));
+            }
+            if (lane == 0 && c) atomicAdd(&sh[4 + bit], c);
+            __syncthreads();
+            const uint32_t ones = sh[4 + bit];
+            if (ones >= need) prefix |= bm;
+            else need -= ones;
+            mask |= bm;
+        }
+        thr = prefix;
+    }
+    // keys > thr are kept; of the keys == thr the first `need` slots
+
+    // ---- ordered emit: slot order is row-major (row j, then wave, then lane)
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const bool in = j * kSelThreads + tid < N;
+        const uint64_t gm = __ballot(in && key[j] > thr), em = __ballot(in && key[j] == thr);
+        if (lane == 0) {
+            row_g[j * kSelWaves + wave] = (uint32_t)__popcll(gm);
+            row_e[j * kSelWaves + wave] = (uint32_t)__popcll(em);
+        }
+    }
+    __syncthreads();
+    {   // exclusive scan over the KPT*16 (row, wave) counts: thread t owns entry t
+        constexpr int kEntries = KPT * kSelWaves;
+        static_assert(kEntries <= kSelThreads, "one thread per (row, wave) entry");
+        uint32_t vg = tid < kEntries ? row_g[tid] : 0u, ve = tid < kEntries ? row_e[tid] : 0u;
+        uint32_t cg = vg, ce = ve;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t tg = __shfl_up(cg, o, 64), te = __shfl_up(ce, o, 64);
+            if (lane >= o) {
+                cg += tg;
+                ce += te;
+            }
+        }
+        if (lane == 63) {
+            scan_tot[0][wave] = cg;
+            scan_tot[1][wave] = ce;
+        }
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) {
+            cg += scan_tot[0][w];
+            ce += scan_tot[1][w];
+        }
+        if (tid < kEntries) {
+            row_g[tid] = cg - vg;
+            row_e[tid] = ce - ve;
+        }
+    }
+    __syncthreads();
+    const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) {
+        const int n = j * kSelThreads + tid;
+        const bool in = n < N;
+        const bool gt = in && key[j] > thr, eq = in && key[j] == thr;
+        const uint64_t gm = __ballot(gt), em = __ballot(eq);
+        const uint32_t g_before = row_g[j * kSelWaves + wave] + (uint32_t)__popcll(gm & below);
+        const uint32_t e_before = row_e[j * kSelWaves + wave] + (uint32_t)__popcll(em & below);
+        if (gt || (eq && e_before < need)) out[g_before + (e_before < need ? e_before : need)] = n;
+    }
+}
+
 template <int G>
 tri_status launch_select_g(const SelectArgs &sa, int n_inst, hipStream_t st)
 {
+    if (sa.max_seq_len <= 8 * kSelThreads) {
+        hipLaunchKernelGGL((select_reg_kernel<G, 8>), dim3(n_inst), dim3(kSelThreads), 0, st, sa);
+        return hip_status("select_reg_kernel");
+    }
+    if (sa.max_seq_len <= 32 * kSelThreads) {
+        hipLaunchKernelGGL((select_reg_kernel<G, 32>), dim3(n_inst), dim3(kSelThreads), 0, st, sa);
+        return hip_status("select_reg_kernel");
+    }
     auto kern = select_kernel<G>;
     const size_t lds = (size_t)sa.lds_keys * sizeof(uint32_t);
     if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
