@@ -25,7 +25,6 @@ namespace {
 constexpr double kTwoPi = 6.283185307179586476925286766559;
 constexpr int kFastThreads = 512;
 constexpr int kFastWaves = kFastThreads / 64;
-constexpr int kWaveKeys = kFastChunk / kFastWaves;   // contiguous keys per wave
 
 typedef float float4v __attribute__((ext_vector_type(4)));
 
@@ -119,7 +118,8 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
     for (int q = 0; q < NG; ++q) out[q] = reduce_blocks(acc[q]);
 }
 
-// grid (ceil(Nmax / kFastChunk), S*Hkv, L), block 512.  Each wave walks kWaveKeys contiguous keys in
+// grid (ceil(Nmax / kFastChunk), S*Hkv, L), block 512.  The workgroup's keys (8192, fewer in the last
+// chunk of a sequence) are split evenly over its 8 waves; each wave walks its contiguous share in
 // groups of 16 (4 steps).  PAGED: block_size >= 16, so a group never straddles a block.
 template <int G, bool PAGED>
 __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
@@ -158,8 +158,10 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
             tb[q].cn[k] = on ? lds_tab[(f * 3 + 2) * G + g] : 0.f;
         }
 
-    const int w0 = chunk * kFastChunk + wave * kWaveKeys;
-    const int w1 = min(w0 + kWaveKeys, N);
+    const int c0 = chunk * kFastChunk, c_len = min(N - c0, kFastChunk);
+    const int wave_keys = ((c_len + kFastWaves - 1) / kFastWaves + 15) & ~15;   // multiple of 16: groups stay aligned
+    const int w0 = c0 + wave * wave_keys;
+    const int w1 = min(w0 + wave_keys, c0 + c_len);
     const char *ph0 = (const char *)lds_phasors + b * kPhasorBlockStride;
     const int Hq = c.n_kv_heads * G;
     float *rw = a.raw + (((int64_t)l * c.n_seqs + s) * Hq + (int64_t)h * G) * c.max_seq_len;

@@ -68,6 +68,10 @@ CONFIGS = {
                        min_seq_len=4096, block_size=16, seed=SEED_BASE + 4),
     "c5_long": Config("c5_long", 64, 1, 64, 8, 128, 1e6, 131072, 4096, 32, "bf16", "dense",
                       outlier_p=0.05, outlier_scale=10.0, seed=SEED_BASE + 5),
+    # Steady state of the paper's policy (Section 4.3): budget + one window of 128 new tokens per head-instance,
+    # survivors at scattered positions; many short head-instances instead of few long ones.
+    "steady_state": Config("steady_state", 36, 64, 32, 8, 128, 1e6, 2176, 2048, 16, "bf16", "sparse",
+                           seed=SEED_BASE + 6),
 }
 
 
