@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--cpu-instances", type=int, default=4, help="head-instances the CPU oracle is timed on")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--split", action="store_true", help="call the three entry points instead of the fused one")
+    ap.add_argument("--fill", action="store_true",
+                    help="evict in place with the fewest moves (tri_compact_fill) instead of the ordered compaction")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic for scaling rocprofv3 byte counters)")
     ap.add_argument("--hbm-probe", action="store_true",
@@ -68,7 +70,9 @@ def main():
     centers = torch.empty((L, Hq, d // 2, 3), dtype=torch.float32, device=dev)
     T.tri_build_centers(model, w["q_samples"], centers)
     paged = "block_table" in w
-    if paged:   # in place: the survivors go to the front blocks of the same pools
+    if args.fill:
+        dst = None
+    elif paged:   # in place: the survivors go to the front blocks of the same pools
         dst = src
     else:
         kd = torch.empty((L, S, Hkv, B, d), dtype=w["k"].dtype, device=dev)
@@ -92,7 +96,10 @@ def main():
         if args.split:
             T.tri_score(model, centers, src, final, None, ws)
             T.tri_select_topk(model, final, src, B, kept_idx, kept_cnt, ws)
-            T.tri_compact(model, src, dst, B, kept_idx, kept_cnt, new_len)
+            if dst is None:
+                T.tri_compact_fill(model, src, B, kept_idx, kept_cnt, new_len)
+            else:
+                T.tri_compact(model, src, dst, B, kept_idx, kept_cnt, new_len)
         else:
             T.tri_compress_step(model, centers, src, dst, B, kept_idx, kept_cnt, new_len, ws)
 
@@ -133,6 +140,9 @@ def main():
     bytes_per_launch = (eb * d + 4) * keys / launches
     achieved = bytes_per_launch / (launch_ms * 1e-3) / 1e9
     step_bytes = int(sum(STEP_BYTES(int(n), B) for n in lens)) * L * Hkv if eb == 2 else None
+    if args.fill and step_bytes:   # only the kept keys stored beyond the new length move
+        moved = int((kept_idx >= kept_cnt[..., None]).sum())
+        step_bytes = 260 * keys + 1032 * moved
     roofline = {"bound": "hbm", "kernel": "score_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get("%s/%s" % (cfg.name, mode)),
@@ -154,6 +164,7 @@ def main():
                       "q_heads": Hq, "head_dim": d, "keys_per_seq": cfg.seq_len, "budget": B,
                       "n_offsets": cfg.n_offsets, "storage": cfg.dtype, "layout": "paged16" if paged else "contiguous",
                       "keys": keys, "entry": "split" if args.split else "tri_compress_step",
+                      "compaction": "fill" if args.fill else "ordered",
                       "generate_s": round(t_gen, 1)},
            "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(out), flush=True)

@@ -148,9 +148,21 @@ tri_status tri_compact(const tri_model *model, const tri_cache *src, const tri_c
                        int32_t *new_seq_len, void *stream);
 
 /*
- * Steps 1-4 in one call, pipelined over layers so that the per-layer score arrays stay in
- * cache between the kernels.  Same arguments and results as the three calls above; raw and
- * final scores live in the workspace only.
+ * Step 4 for callers that do not need the survivors in slot order (attention treats the cached keys as a set;
+ * each key carries its own position): in-place eviction that moves as few slots as possible.  Kept keys that
+ * already sit in slots [0, kept_cnt) stay where they are; the i-th free slot below kept_cnt (ascending)
+ * receives the i-th kept key stored at or beyond kept_cnt (ascending), with its V row and position.  In the
+ * steady state of Section 4.3 (a budget of keys plus one window of 128 new tokens) this moves at most 128 slots
+ * per head-instance instead of nearly all of them.  Arguments as tri_compact with dst = src = cache.
+ */
+tri_status tri_compact_fill(const tri_model *model, const tri_cache *cache, int32_t budget,
+                            const int32_t *kept_idx, const int32_t *kept_cnt, int32_t *new_seq_len,
+                            void *stream);
+
+/*
+ * Steps 1-4 in one call.  Same arguments and results as the three calls above; raw scores and
+ * their statistics live in the workspace only and the selection forms the final scores itself.
+ * dst == NULL evicts in place with tri_compact_fill (fewest moves, slot order not preserved).
  */
 tri_status tri_compress_step(const tri_model *model, const float *centers, const tri_cache *src,
                              const tri_cache *dst, int32_t budget, int32_t *kept_idx,

@@ -310,6 +310,31 @@ int tri_oracle_compact_rows(const void *src, int64_t src_stride_bytes, int64_t r
     return 0;
 }
 
+/*
+ * Eviction that moves as few slots as possible (same passage; the paper fixes no slot order): the kept
+ * keys that already sit in slots [0, cnt) stay; the i-th free slot below cnt (ascending) receives the
+ * i-th kept key stored at or beyond cnt (ascending).  rows: K or V or positions, row n at byte n*stride.
+ */
+int tri_oracle_compact_fill(void *rows, int64_t stride_bytes, int64_t row_bytes, const int32_t *idx, int32_t cnt)
+{
+    char *kept = (char *)calloc((size_t)(cnt > 0 ? cnt : 1), 1);
+    if (!kept) return -2;
+    int32_t first_tail = cnt;   /* first entry of idx that lies at or beyond cnt */
+    for (int32_t j = 0; j < cnt; ++j) {
+        if (idx[j] < cnt) kept[idx[j]] = 1;
+        else if (first_tail == cnt) first_tail = j;
+    }
+    int32_t t = first_tail;
+    for (int32_t hole = 0; hole < cnt && t < cnt; ++hole) {
+        if (kept[hole]) continue;
+        memcpy((char *)rows + (int64_t)hole * stride_bytes, (const char *)rows + (int64_t)idx[t] * stride_bytes,
+               (size_t)row_bytes);
+        ++t;
+    }
+    free(kept);
+    return 0;
+}
+
 /* ---- paged layout (block table; not in the paper, a storage choice) ---- */
 
 /* element offset of slot n of (layer, sequence, head) in a paged pool */

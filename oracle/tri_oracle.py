@@ -60,6 +60,8 @@ def lib():
         L.tri_oracle_topk.argtypes = [vp, i64, i64, vp, vp]
         L.tri_oracle_compact_rows.restype = i32
         L.tri_oracle_compact_rows.argtypes = [vp, i64, i64, vp, i32, vp, i64]
+        L.tri_oracle_compact_fill.restype = i32
+        L.tri_oracle_compact_fill.argtypes = [vp, i64, i64, vp, i32]
         L.tri_oracle_paged_gather.restype = i32
         L.tri_oracle_paged_gather.argtypes = [vp, i64, i64, vp, i32, i32, i64, i64, i64, i64, i32, i32, i32, i64, vp]
         L.tri_oracle_paged_compact.restype = i32
@@ -186,6 +188,15 @@ def compact_rows(src, idx, out=None):
                                        out.strides[0])
     assert rc == 0
     return out
+
+
+def compact_fill(rows, idx):
+    """In place on a 2-D C-contiguous array: the kept rows at or beyond len(idx) fill the free slots below it."""
+    assert rows.ndim == 2 and rows.flags.c_contiguous
+    idx = _c(idx, np.int32)
+    rc = lib().tri_oracle_compact_fill(_ptr(rows), rows.strides[0], rows.shape[1] * rows.itemsize, _ptr(idx), len(idx))
+    assert rc == 0
+    return rows
 
 
 def paged_gather(pool, row_elems, block_table, block_size, strides, layer, seq, head, N):

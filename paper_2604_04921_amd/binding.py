@@ -17,7 +17,7 @@ TRI_F32, TRI_BF16 = 0, 1
 TRI_PAIR_INTERLEAVED, TRI_PAIR_HALF = 0, 1
 
 EXPORTS = ["tri_last_error", "tri_build_centers", "tri_workspace_size", "tri_score", "tri_select_topk",
-           "tri_compact", "tri_compress_step", "tri_timing_attach", "tri_timing_detach"]
+           "tri_compact", "tri_compact_fill", "tri_compress_step", "tri_timing_attach", "tri_timing_detach"]
 
 
 class TriModel(ctypes.Structure):
@@ -69,6 +69,8 @@ def lib():
         L.tri_compact.restype = i32
         L.tri_compact.argtypes = [ctypes.POINTER(TriModel), ctypes.POINTER(TriCache), ctypes.POINTER(TriCache), i32,
                                   vp, vp, vp, vp]
+        L.tri_compact_fill.restype = i32
+        L.tri_compact_fill.argtypes = [ctypes.POINTER(TriModel), ctypes.POINTER(TriCache), i32, vp, vp, vp, vp]
         L.tri_compress_step.restype = i32
         L.tri_compress_step.argtypes = [ctypes.POINTER(TriModel), vp, ctypes.POINTER(TriCache),
                                         ctypes.POINTER(TriCache), i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -170,8 +172,13 @@ def tri_compact(model, src, dst, budget, kept_idx, kept_cnt, new_seq_len=None, s
                              _stream(stream)))
 
 
+def tri_compact_fill(model, cache, budget, kept_idx, kept_cnt, new_seq_len=None, stream=None):
+    _check(lib().tri_compact_fill(model.ref, cache.ref, int(budget), _p(kept_idx), _p(kept_cnt), _p(new_seq_len),
+                                  _stream(stream)))
+
+
 def tri_compress_step(model, centers, src, dst, budget, kept_idx, kept_cnt, new_seq_len, workspace, stream=None):
-    _check(lib().tri_compress_step(model.ref, _p(centers), src.ref, dst.ref, int(budget), _p(kept_idx), _p(kept_cnt),
+    _check(lib().tri_compress_step(model.ref, _p(centers), src.ref, dst.ref if dst is not None else None, int(budget), _p(kept_idx), _p(kept_cnt),
                                    _p(new_seq_len), _p(workspace), workspace.numel() * workspace.element_size(),
                                    _stream(stream)))
 

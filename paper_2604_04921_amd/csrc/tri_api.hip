@@ -292,6 +292,19 @@ tri_status tri_compact(const tri_model *model, const tri_cache *src, const tri_c
     return launch_compact(*model, *src, d, budget, kept_idx, kept_cnt, new_seq_len, (hipStream_t)stream);
 }
 
+tri_status tri_compact_fill(const tri_model *model, const tri_cache *cache, int32_t budget,
+                            const int32_t *kept_idx, const int32_t *kept_cnt, int32_t *new_seq_len, void *stream)
+{
+    tri_status rc = check_model(model);
+    if (rc != TRI_OK) return rc;
+    if ((rc = check_cache(model, cache, true, "tri_compact_fill")) != TRI_OK) return rc;
+    if (!kept_idx || !kept_cnt || budget < 1) {
+        set_error("tri_compact_fill: kept_idx, kept_cnt and budget >= 1 required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    return launch_compact_fill(*model, *cache, budget, kept_idx, kept_cnt, new_seq_len, (hipStream_t)stream);
+}
+
 tri_status tri_compress_step(const tri_model *model, const float *centers, const tri_cache *src,
                              const tri_cache *dst, int32_t budget, int32_t *kept_idx, int32_t *kept_cnt,
                              int32_t *new_seq_len, void *workspace, size_t ws_bytes, void *stream)
@@ -299,8 +312,8 @@ tri_status tri_compress_step(const tri_model *model, const float *centers, const
     tri_status rc = check_model(model);
     if (rc != TRI_OK) return rc;
     if ((rc = check_cache(model, src, true, "tri_compress_step src")) != TRI_OK) return rc;
-    if (!centers || !dst || !kept_idx || !kept_cnt || budget < 1) {
-        set_error("tri_compress_step: centers, dst, kept_idx, kept_cnt and budget >= 1 required");
+    if (!centers || !kept_idx || !kept_cnt || budget < 1) {
+        set_error("tri_compress_step: centers, kept_idx, kept_cnt and budget >= 1 required");
         return TRI_ERR_INVALID_ARG;
     }
     const Workspace wl = workspace_layout(*model, *src, budget);
@@ -313,6 +326,7 @@ tri_status tri_compress_step(const tri_model *model, const float *centers, const
                             reinterpret_cast<uint32_t *>(ws + wl.final_), *src, budget, kept_idx, kept_cnt,
                             (hipStream_t)stream)) != TRI_OK)
         return rc;
+    if (!dst) return tri_compact_fill(model, src, budget, kept_idx, kept_cnt, new_seq_len, stream);
     return tri_compact(model, src, dst, budget, kept_idx, kept_cnt, new_seq_len, stream);
 }
 

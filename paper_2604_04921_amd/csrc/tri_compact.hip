@@ -121,7 +121,120 @@ __global__ __launch_bounds__(kInplaceThreads) void inplace_kernel(CompactArgs a)
     }
 }
 
+constexpr int kFillThreads = 256;
+constexpr int kFillMaxWords = 2048;   // budget <= 65536
+
+// In-place eviction that moves as few slots as possible (Section 4.3 fixes no slot order): kept keys already in
+// slots [0, cnt) stay; the i-th free slot below cnt (ascending) receives the i-th kept key stored at or beyond
+// cnt (ascending).  Sources (>= cnt) and destinations (< cnt) are disjoint, so the moves need no ordering.
+// grid (instances), block 256, dynamic LDS 8 * budget bytes (the move list).
+__global__ __launch_bounds__(kFillThreads) void fill_kernel(CompactArgs a)
+{
+    extern __shared__ int32_t moves[];   // [2][budget]: destination slots, source slots
+    __shared__ uint32_t kept_bits[kFillMaxWords];
+    __shared__ uint32_t wave_tot[kFillThreads / 64];
+    __shared__ int32_t n_tail;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int inst = blockIdx.x;
+    int l, s, h;
+    decode_inst(a.src, inst, l, s, h);
+    const int cnt = a.kept_cnt[inst];
+    write_new_len(a, l, s, h, cnt);
+    const int32_t *idx = a.kept_idx + (int64_t)inst * a.budget;
+    const int n_words = (cnt + 31) >> 5;
+    for (int w = tid; w < n_words; w += kFillThreads) kept_bits[w] = 0u;
+    if (tid == 0) n_tail = 0;
+    __syncthreads();
+    int my_tail = 0;
+    for (int j = tid; j < cnt; j += kFillThreads) {
+        const int n = idx[j];
+        if (n < cnt) atomicOr(&kept_bits[n >> 5], 1u << (n & 31));
+        else ++my_tail;
+    }
+    if (my_tail) atomicAdd(&n_tail, my_tail);
+    __syncthreads();
+    const int first_tail = cnt - n_tail;   // idx is ascending: its last n_tail entries lie at or beyond cnt
+    // free slots below cnt, in ascending order, paired with the tail survivors
+    int done = 0;
+    for (int w0 = 0; w0 < n_words; w0 += kFillThreads) {
+        const int w = w0 + tid;
+        uint32_t free_bits = 0u;
+        if (w < n_words) {
+            free_bits = ~kept_bits[w];
+            if (w == n_words - 1 && (cnt & 31)) free_bits &= (1u << (cnt & 31)) - 1u;
+        }
+        const uint32_t c = (uint32_t)__popc(free_bits);
+        uint32_t cum = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t t = __shfl_up(cum, o, 64);
+            if (lane >= o) cum += t;
+        }
+        if (lane == 63) wave_tot[wave] = cum;
+        __syncthreads();
+        uint32_t before = cum - c, total = 0u;
+        for (int k = 0; k < kFillThreads / 64; ++k) {
+            if (k < wave) before += wave_tot[k];
+            total += wave_tot[k];
+        }
+        int o = done + (int)before;
+        while (free_bits) {
+            const int bit = __ffs(free_bits) - 1;
+            free_bits &= free_bits - 1u;
+            moves[o] = (w << 5) + bit;
+            moves[a.budget + o] = idx[first_tail + o];
+            ++o;
+        }
+        done += (int)total;
+        __syncthreads();
+    }
+    // done == n_tail moves; 16 bytes of K and of V per thread and move
+    const int rows_per_pass = kFillThreads / a.row16;
+    const int r = tid / a.row16, part = tid % a.row16;
+    char *kb = (char *)a.dst.k, *vb = (char *)a.dst.v;
+    int32_t *pb = const_cast<int32_t *>(a.dst.pos);
+    for (int m0 = 0; m0 < done; m0 += rows_per_pass) {
+        const int m = m0 + r;
+        if (m >= done) continue;
+        const int dj = moves[m], sn = moves[a.budget + m];
+        const int64_t so = kv_offset(a.src, l, s, h, sn) * a.elem_bytes + part * 16;
+        const int64_t d_o = kv_offset(a.dst, l, s, h, dj) * a.elem_bytes + part * 16;
+        const uint4 kv = *reinterpret_cast<const uint4 *>(kb + so);
+        const uint4 vv = *reinterpret_cast<const uint4 *>(vb + so);
+        *reinterpret_cast<uint4 *>(kb + d_o) = kv;
+        *reinterpret_cast<uint4 *>(vb + d_o) = vv;
+        if (part == 0) pb[pos_offset(a.dst, l, s, h, dj)] = pb[pos_offset(a.src, l, s, h, sn)];
+    }
+}
+
 }  // namespace
+
+tri_status launch_compact_fill(const tri_model &m, const tri_cache &c, int32_t budget, const int32_t *kept_idx,
+                               const int32_t *kept_cnt, int32_t *new_seq_len, hipStream_t st)
+{
+    const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
+    if (n_inst <= 0) return TRI_OK;
+    if (budget > kFillMaxWords * 32) {
+        set_error("tri_compact_fill: budget %d above %d", budget, kFillMaxWords * 32);
+        return TRI_ERR_UNSUPPORTED;
+    }
+    CompactArgs a{};
+    a.src = make_view(m, c);
+    a.dst = a.src;
+    a.kept_idx = kept_idx;
+    a.kept_cnt = kept_cnt;
+    a.new_seq_len = new_seq_len;
+    a.budget = budget;
+    a.elem_bytes = c.dtype == TRI_BF16 ? 2 : 4;
+    a.row16 = kHeadDim * a.elem_bytes / 16;
+    const size_t lds = (size_t)budget * 8;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute((const void *)fill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return hip_status("hipFuncSetAttribute(fill_kernel)");
+    hipLaunchKernelGGL(fill_kernel, dim3(n_inst), dim3(kFillThreads), lds, st, a);
+    return hip_status("fill_kernel");
+}
 
 tri_status launch_compact(const tri_model &m, const tri_cache &src, const tri_cache &dst, int32_t budget,
                           const int32_t *kept_idx, const int32_t *kept_cnt, int32_t *new_seq_len,

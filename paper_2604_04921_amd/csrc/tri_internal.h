@@ -83,4 +83,7 @@ tri_status launch_compact(const tri_model &m, const tri_cache &src, const tri_ca
                           const int32_t *kept_idx, const int32_t *kept_cnt, int32_t *new_seq_len,
                           hipStream_t st);
 
+tri_status launch_compact_fill(const tri_model &m, const tri_cache &c, int32_t budget, const int32_t *kept_idx,
+                               const int32_t *kept_cnt, int32_t *new_seq_len, hipStream_t st);
+
 }  // namespace tri

@@ -366,3 +366,23 @@ def test_generator_concentration_matches_rice_mean(oracle):
     assert 1.0 / rice_mean == pytest.approx(0.978, abs=1e-3)
     assert R.mean() == pytest.approx(1.0 / rice_mean, abs=2e-3)
     assert 0.97 < R.min() and R.max() < 0.99
+
+
+def test_compact_fill_moves_only_into_holes(oracle):
+    """Minimal-move compaction: afterwards slots [0, cnt) hold exactly the kept rows (as a set), kept rows that
+    were already below cnt have not moved, and the number of rows that changed equals the number of holes."""
+    rng = np.random.default_rng(47)
+    for n, cnt in [(50, 20), (300, 256), (64, 64), (10, 1), (40, 39)]:
+        src = rng.integers(1, 65535, size=(n, 16)).astype(np.uint16)
+        src[:, 0] = np.arange(n)                      # every row distinct
+        idx = np.sort(rng.choice(n, size=cnt, replace=False)).astype(np.int32)
+        out = oracle.compact_fill(src.copy(), idx)
+        assert sorted(out[:cnt, 0].tolist()) == sorted(idx.tolist())
+        stay = idx[idx < cnt]
+        np.testing.assert_array_equal(out[stay], src[stay])
+        holes = cnt - len(stay)
+        assert int(np.any(out[:cnt] != src[:cnt], axis=1).sum()) == holes
+        np.testing.assert_array_equal(out[cnt:], src[cnt:])     # nothing beyond cnt is written
+        # pairing rule: i-th hole (ascending) <- i-th tail survivor (ascending)
+        hole_slots = np.setdiff1d(np.arange(cnt), stay)
+        np.testing.assert_array_equal(out[hole_slots], src[idx[idx >= cnt]])
