@@ -31,7 +31,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c3_model")
-    ap.add_argument("--positions", default=None, choices=[None, "dense", "sparse"])
+    ap.add_argument("--positions", default=None, choices=[None, "dense", "sparse", "sparse16", "scattered"])
     ap.add_argument("--layers", type=int, default=None, help="layer slab (configurations larger than HBM)")
     ap.add_argument("--cpu-instances", type=int, default=4, help="head-instances the CPU oracle is timed on")
     ap.add_argument("--no-cpu", action="store_true")

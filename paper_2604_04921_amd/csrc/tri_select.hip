@@ -201,14 +201,16 @@ __device__ __forceinline__ int linear_bin(uint32_t u)
     return (int)fminf(fmaxf(x, 0.0f), 2047.0f);
 }
 
-template <int G, int KPT>
-__global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
+template <int G, int KPT, int THREADS>
+__global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
 {
+    constexpr int kWaves = THREADS / 64;
+    constexpr int kBinsPerThread = kSelBins / THREADS;
     __shared__ uint32_t hist[kSelBins];
     __shared__ uint32_t cand_key[kSelCand];
     __shared__ int32_t cand_idx[kSelCand];
-    __shared__ uint32_t row_g[KPT * kSelWaves], row_e[KPT * kSelWaves];   // [row j][wave], then exclusive prefixes
-    __shared__ uint32_t scan_tot[2][kSelWaves];
+    __shared__ uint32_t row_g[KPT * kWaves], row_e[KPT * kWaves];   // [row j][wave], then exclusive prefixes
+    __shared__ uint32_t scan_tot[2][kWaves];
     __shared__ uint32_t sh[36];   // 0: selected bin, 1: need inside it, 2: candidate count, 3: threshold key, 4..35: bit counters / tie count
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -220,10 +222,10 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
     int32_t *out = a.kept_idx + (int64_t)inst * B;
     if (tid == 0) a.kept_cnt[inst] = N < B ? N : B;
     if (N <= B) {  // nothing to evict: keep every slot
-        for (int n = tid; n < N; n += kSelThreads) out[n] = n;
+        for (int n = tid; n < N; n += THREADS) out[n] = n;
         return;
     }
-    for (int k = tid; k < kSelBins; k += kSelThreads) hist[k] = 0u;
+    for (int k = tid; k < kSelBins; k += THREADS) hist[k] = 0u;
     if (tid < 36) sh[tid] = 0u;
     __syncthreads();
 
@@ -242,7 +244,7 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
         }
 #pragma unroll
         for (int j = 0; j < KPT; ++j) {
-            const int n = j * kSelThreads + tid;
+            const int n = j * THREADS + tid;
             key[j] = 0u;
             if (n < N) {
                 float f;
@@ -262,10 +264,16 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
     }
     __syncthreads();
 
-    // ---- the bin holding the B-th largest: thread t owns bins 2047-2t and 2046-2t
+    // ---- the bin holding the B-th largest: thread t owns bins 2047 - t*kBinsPerThread and the ones just below
     {
-        const uint32_t v0 = hist[kSelBins - 1 - 2 * tid], v1 = hist[kSelBins - 2 - 2 * tid];
-        uint32_t cum = v0 + v1;
+        uint32_t v[kBinsPerThread];
+        uint32_t cum = 0u;
+#pragma unroll
+        for (int k = 0; k < kBinsPerThread; ++k) {
+            v[k] = hist[kSelBins - 1 - kBinsPerThread * tid - k];
+            cum += v[k];
+        }
+        const uint32_t own = cum;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
             const uint32_t t = __shfl_up(cum, o, 64);
@@ -274,13 +282,15 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
         if (lane == 63) scan_tot[0][wave] = cum;
         __syncthreads();
         for (int w = 0; w < wave; ++w) cum += scan_tot[0][w];
-        const uint32_t excl = cum - v0 - v1, need = (uint32_t)B;
-        if (excl < need && need <= excl + v0) {
-            sh[0] = (uint32_t)(kSelBins - 1 - 2 * tid);
-            sh[1] = need - excl;
-        } else if (excl + v0 < need && need <= cum) {
-            sh[0] = (uint32_t)(kSelBins - 2 - 2 * tid);
-            sh[1] = need - excl - v0;
+        uint32_t excl = cum - own;
+        const uint32_t need = (uint32_t)B;
+#pragma unroll
+        for (int k = 0; k < kBinsPerThread; ++k) {
+            if (excl < need && need <= excl + v[k]) {
+                sh[0] = (uint32_t)(kSelBins - 1 - kBinsPerThread * tid - k);
+                sh[1] = need - excl;
+            }
+            excl += v[k];
         }
     }
     __syncthreads();
@@ -290,7 +300,7 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
     // ---- gather the selected bin's keys (any order; ranks below do not depend on it)
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
-        const int n = j * kSelThreads + tid;
+        const int n = j * THREADS + tid;
         const bool hit = n < N && linear_bin(key[j]) == sel_bin;
         const uint64_t hm = __ballot(hit);
         if (hm) {
@@ -309,7 +319,7 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
     uint32_t thr;
     if (m <= (uint32_t)kSelCand) {
         // exact rank of every candidate among the candidates: key descending, slot ascending
-        for (uint32_t c = tid; c < m; c += kSelThreads) {
+        for (uint32_t c = tid; c < m; c += THREADS) {
             const uint32_t kc = cand_key[c];
             const int32_t ic = cand_idx[c];
             uint32_t rank = 0u;
@@ -323,7 +333,7 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
         thr = sh[3];
         // threshold ties kept = need - (candidates strictly above the threshold)
         uint32_t above = 0u;
-        for (uint32_t c = tid; c < m; c += kSelThreads) above += cand_key[c] > thr ? 1u : 0u;
+        for (uint32_t c = tid; c < m; c += THREADS) above += cand_key[c] > thr ? 1u : 0u;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) above += __shfl_xor(above, o, 64);
         if (lane == 0 && above) atomicAdd(&sh[4], above);
@@ -338,7 +348,7 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
             uint32_t c = 0u;
 #pragma unroll
             for (int j = 0; j < KPT; ++j) {
-                const bool in = j * kSelThreads + tid < N && linear_bin(key[j]) == sel_bin;
+                const bool in = j * THREADS + tid < N && linear_bin(key[j]) == sel_bin;
                 c += (uint32_t)__popcll(__ballot(in && (key[j] & mask) == prefix && (key[j] & bm) != 0u));
             }
             if (lane == 0 && c) atomicAdd(&sh[4 + bit], c);
@@ -355,17 +365,17 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
     // ---- ordered emit: slot order is row-major (row j, then wave, then lane)
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
-        const bool in = j * kSelThreads + tid < N;
+        const bool in = j * THREADS + tid < N;
         const uint64_t gm = __ballot(in && key[j] > thr), em = __ballot(in && key[j] == thr);
         if (lane == 0) {
-            row_g[j * kSelWaves + wave] = (uint32_t)__popcll(gm);
-            row_e[j * kSelWaves + wave] = (uint32_t)__popcll(em);
+            row_g[j * kWaves + wave] = (uint32_t)__popcll(gm);
+            row_e[j * kWaves + wave] = (uint32_t)__popcll(em);
         }
     }
     __syncthreads();
     {   // exclusive scan over the KPT*16 (row, wave) counts: thread t owns entry t
-        constexpr int kEntries = KPT * kSelWaves;
-        static_assert(kEntries <= kSelThreads, "one thread per (row, wave) entry");
+        constexpr int kEntries = KPT * kWaves;
+        static_assert(kEntries <= THREADS, "one thread per (row, wave) entry");
         uint32_t vg = tid < kEntries ? row_g[tid] : 0u, ve = tid < kEntries ? row_e[tid] : 0u;
         uint32_t cg = vg, ce = ve;
 #pragma unroll
@@ -394,12 +404,12 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
     const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
-        const int n = j * kSelThreads + tid;
+        const int n = j * THREADS + tid;
         const bool in = n < N;
         const bool gt = in && key[j] > thr, eq = in && key[j] == thr;
         const uint64_t gm = __ballot(gt), em = __ballot(eq);
-        const uint32_t g_before = row_g[j * kSelWaves + wave] + (uint32_t)__popcll(gm & below);
-        const uint32_t e_before = row_e[j * kSelWaves + wave] + (uint32_t)__popcll(em & below);
+        const uint32_t g_before = row_g[j * kWaves + wave] + (uint32_t)__popcll(gm & below);
+        const uint32_t e_before = row_e[j * kWaves + wave] + (uint32_t)__popcll(em & below);
         if (gt || (eq && e_before < need)) out[g_before + (e_before < need ? e_before : need)] = n;
     }
 }
@@ -407,12 +417,16 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(SelectArgs a)
 template <int G>
 tri_status launch_select_g(const SelectArgs &sa, int n_inst, hipStream_t st)
 {
+    if (sa.max_seq_len <= 16 * 256) {   // short sequences: small workgroups, cheap barriers, many per CU
+        hipLaunchKernelGGL((select_reg_kernel<G, 16, 256>), dim3(n_inst), dim3(256), 0, st, sa);
+        return hip_status("select_reg_kernel");
+    }
     if (sa.max_seq_len <= 8 * kSelThreads) {
-        hipLaunchKernelGGL((select_reg_kernel<G, 8>), dim3(n_inst), dim3(kSelThreads), 0, st, sa);
+        hipLaunchKernelGGL((select_reg_kernel<G, 8, kSelThreads>), dim3(n_inst), dim3(kSelThreads), 0, st, sa);
         return hip_status("select_reg_kernel");
     }
     if (sa.max_seq_len <= 32 * kSelThreads) {
-        hipLaunchKernelGGL((select_reg_kernel<G, 32>), dim3(n_inst), dim3(kSelThreads), 0, st, sa);
+        hipLaunchKernelGGL((select_reg_kernel<G, 32, kSelThreads>), dim3(n_inst), dim3(kSelThreads), 0, st, sa);
         return hip_status("select_reg_kernel");
     }
     auto kern = select_kernel<G>;

@@ -73,7 +73,8 @@ def fill_normal(out, seed, tag):
 def generate(cfg, positions=None, layers=None):
     """The workload of `cfg` on cuda:0 as torch tensors.
 
-    positions overrides cfg.positions ("dense" / "sparse"); layers overrides cfg.n_layers (layer slabs
+    positions overrides cfg.positions ("dense"; "sparse" / "sparse16": sorted unique draws from [0, 2N) / [0, 16N);
+    "scattered": the draws of "sparse16" left in random slot order); layers overrides cfg.n_layers (layer slabs
     for configurations that do not fit in HBM at once).  Returns a dict with q_samples, k, v, pos,
     seq_len, cur_pos and, for paged configurations, block_table (k, v, pos are then block pools)."""
     L = cfg.n_layers if layers is None else layers
@@ -89,7 +90,8 @@ def generate(cfg, positions=None, layers=None):
     out["q_samples"] = q
     lens = recipe.seq_lens(cfg)
     out["seq_len"] = torch.from_numpy(lens).cuda()
-    cur = lens.copy() if mode == "dense" else 2 * lens
+    spread = {"dense": 1, "sparse": 2, "sparse16": 16, "scattered": 16}[mode]
+    cur = spread * lens
     out["cur_pos"] = torch.from_numpy(cur.astype(np.int32)).cuda()
     if cfg.block_size:
         bs = cfg.block_size
@@ -118,9 +120,11 @@ def generate(cfg, positions=None, layers=None):
             g = torch.Generator(device="cuda")
             g.manual_seed(cfg.seed + 6)
             pos = torch.empty((L, S, Hkv, N), dtype=torch.int32, device="cuda")
-            for l in range(L):      # sorted unique draws from [0, 2N) per head-instance
-                r = torch.rand((S * Hkv, 2 * N), generator=g, device="cuda")
-                sel = r.argsort(dim=1)[:, :N].sort(dim=1).values
+            for l in range(L):      # unique draws from [0, spread * N) per head-instance
+                r = torch.rand((S * Hkv, spread * N), generator=g, device="cuda")
+                sel = r.argsort(dim=1)[:, :N]
+                if mode != "scattered":   # "scattered": slot order unrelated to position (after minimal-move evictions)
+                    sel = sel.sort(dim=1).values
                 pos[l] = sel.to(torch.int32).view(S, Hkv, N)
                 del r, sel
     out["k"], out["v"], out["pos"] = k, v, pos
