@@ -33,6 +33,7 @@
 
 #define ORACLE_F32 0
 #define ORACLE_BF16 1
+#define ORACLE_F64 2 /* keys this file has un-rotated itself (post-RoPE caches) */
 #define ORACLE_PAIR_INTERLEAVED 0
 #define ORACLE_PAIR_HALF 1
 
@@ -45,6 +46,7 @@ static double load_elem(const void *base, int dtype, int64_t idx)
         memcpy(&f, &bits, sizeof f);
         return (double)f;
     }
+    if (dtype == ORACLE_F64) return ((const double *)base)[idx];
     return (double)((const float *)base)[idx];
 }
 
@@ -200,6 +202,109 @@ int tri_oracle_raw_scores(const float *stats, int G, const void *K, int dtype, i
             raw[(int64_t)g * N + n] =
                 tri_oracle_score_avg(stats + (int64_t)g * F * 3, K, dtype, n * row_stride, d, pairs,
                                      theta, cur_pos, (int64_t)pos[n], offsets, n_off);
+    return 0;
+}
+
+/*
+ * Section 4.1, the norm score before the concentration weighting ("w/o R" in the
+ * ablation of Section 5):
+ *   S_norm^(0)(k) = sum_f E||q_f|| * ||k_f||
+ */
+double tri_oracle_s_norm0(const float *stats, const void *key, int dtype, int64_t first, int d,
+                          int pairs)
+{
+    int F = d / 2;
+    double s = 0.0;
+    for (int f = 0; f < F; ++f) {
+        double qabs = (double)stats[3 * f + 2];
+        double kre, kim;
+        load_band(key, dtype, first, d, pairs, f, &kre, &kim);
+        s += qabs * hypot(kre, kim);
+    }
+    return s;
+}
+
+/*
+ * The scoring variants the ablation study removes a component from (Section 5,
+ * ablations of the scoring components and of the adaptive weighting):
+ *   0  S_trig + S_norm          the method
+ *   1  S_trig                   "w/o S_norm"
+ *   2  S_norm                   "w/o S_trig"
+ *   3  S_trig + S_norm^(0)      "w/o R"
+ * each averaged over the future offsets exactly as in tri_oracle_score_avg.
+ */
+double tri_oracle_score_avg_variant(const float *stats, const void *key, int dtype, int64_t first,
+                                    int d, int pairs, double theta, int64_t p_q, int64_t p_k,
+                                    const int64_t *offsets, int n_off, int variant)
+{
+    int64_t Delta = p_q - p_k;
+    double acc = 0.0;
+    for (int j = 0; j < n_off; ++j) {
+        double S = 0.0;
+        if (variant != 2) S += tri_oracle_s_trig(stats, key, dtype, first, d, pairs, theta, Delta + offsets[j]);
+        if (variant == 0 || variant == 2) S += tri_oracle_s_norm(stats, key, dtype, first, d, pairs);
+        if (variant == 3) S += tri_oracle_s_norm0(stats, key, dtype, first, d, pairs);
+        acc += S;
+    }
+    return acc / (double)n_off;
+}
+
+/*
+ * A key read from a post-RoPE cache: the stored vector is R(p_k) k, every band
+ * rotated by omega_f * p_k with the 2x2 matrix of Section 2.1 Eq. 1.  The inverse
+ * of that matrix (its transpose) gives back the pre-RoPE key the scores are
+ * defined on.  out: d doubles, laid out like the stored vector.
+ */
+void tri_oracle_unrotate_key(const void *key, int dtype, int64_t first, int d, int pairs,
+                             double theta, int64_t p_k, double *out)
+{
+    int F = d / 2;
+    for (int f = 0; f < F; ++f) {
+        double xr, xi;
+        load_band(key, dtype, first, d, pairs, f, &xr, &xi);
+        double ang = tri_oracle_omega(theta, d, f) * (double)p_k;
+        double c = cos(ang), s = sin(ang);
+        double kr = c * xr + s * xi;  /* transpose of [[c, -s], [s, c]] */
+        double ki = -s * xr + c * xi;
+        if (pairs == ORACLE_PAIR_HALF) {
+            out[f] = kr;
+            out[f + F] = ki;
+        } else {
+            out[2 * f] = kr;
+            out[2 * f + 1] = ki;
+        }
+    }
+}
+
+/*
+ * tri_oracle_raw_scores with a scoring variant (see tri_oracle_score_avg_variant) and,
+ * with rotated != 0, for a cache that stores post-RoPE keys.
+ */
+int tri_oracle_raw_scores_ex(const float *stats, int G, const void *K, int dtype, int64_t row_stride,
+                             const int32_t *pos, int64_t N, int64_t cur_pos, int d, int pairs,
+                             double theta, const int64_t *offsets, int n_off, int variant, int rotated,
+                             double *raw)
+{
+    if (d <= 0 || (d & 1) || n_off <= 0 || G <= 0 || variant < 0 || variant > 3) return -1;
+    int F = d / 2;
+    double *tmp = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!tmp) return -2;
+    for (int64_t n = 0; n < N; ++n) {
+        const void *key = K;
+        int kd = dtype;
+        int64_t first = n * row_stride;
+        if (rotated) {
+            tri_oracle_unrotate_key(K, dtype, first, d, pairs, theta, (int64_t)pos[n], tmp);
+            key = tmp;
+            kd = ORACLE_F64;
+            first = 0;
+        }
+        for (int g = 0; g < G; ++g)
+            raw[(int64_t)g * N + n] =
+                tri_oracle_score_avg_variant(stats + (int64_t)g * F * 3, key, kd, first, d, pairs, theta,
+                                             cur_pos, (int64_t)pos[n], offsets, n_off, variant);
+    }
+    free(tmp);
     return 0;
 }
 

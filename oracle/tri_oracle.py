@@ -46,7 +46,7 @@ def lib():
         L.tri_oracle_centers.argtypes = [vp, i32, i64, i32, i32, i32, i32, vp]
         L.tri_oracle_s_trig.restype = dbl
         L.tri_oracle_s_trig.argtypes = [vp, vp, i32, i64, i32, i32, dbl, i64]
-        for name in ("tri_oracle_s_norm", "tri_oracle_s_norm_mrl"):
+        for name in ("tri_oracle_s_norm", "tri_oracle_s_norm_mrl", "tri_oracle_s_norm0"):
             fn = getattr(L, name)
             fn.restype = dbl
             fn.argtypes = [vp, vp, i32, i64, i32, i32]
@@ -54,6 +54,10 @@ def lib():
         L.tri_oracle_score_avg.argtypes = [vp, vp, i32, i64, i32, i32, dbl, i64, i64, vp, i32]
         L.tri_oracle_raw_scores.restype = i32
         L.tri_oracle_raw_scores.argtypes = [vp, i32, vp, i32, i64, vp, i64, i64, i32, i32, dbl, vp, i32, vp]
+        L.tri_oracle_raw_scores_ex.restype = i32
+        L.tri_oracle_raw_scores_ex.argtypes = [vp, i32, vp, i32, i64, vp, i64, i64, i32, i32, dbl, vp, i32, i32, i32, vp]
+        L.tri_oracle_unrotate_key.restype = None
+        L.tri_oracle_unrotate_key.argtypes = [vp, i32, i64, i32, i32, dbl, i64, vp]
         L.tri_oracle_gqa_final.restype = i32
         L.tri_oracle_gqa_final.argtypes = [vp, i32, i64, vp, vp, vp]
         L.tri_oracle_topk.restype = i32
@@ -123,8 +127,28 @@ def score_avg(stats, key, theta, p_q, p_k, offsets, pairs=PAIR_INTERLEAVED):
                                       float(theta), int(p_q), int(p_k), _ptr(off), len(off))
 
 
-def raw_scores(stats, K, pos, cur_pos, theta, offsets, pairs=PAIR_INTERLEAVED, threads=1):
+VARIANT_FULL, VARIANT_TRIG_ONLY, VARIANT_NORM_ONLY, VARIANT_NORM_UNWEIGHTED = 0, 1, 2, 3
+
+
+def s_norm0(stats, key, pairs=PAIR_INTERLEAVED):
+    stats = _c(stats, np.float32)
+    key = _c(key)
+    return lib().tri_oracle_s_norm0(_ptr(stats), _ptr(key), _dtype_code(key), 0, key.shape[-1], pairs)
+
+
+def unrotate_key(key, theta, p_k, pairs=PAIR_INTERLEAVED):
+    """A stored post-RoPE key [d] -> the pre-RoPE key, float64 [d]."""
+    key = _c(key)
+    out = np.empty(key.shape[-1], dtype=np.float64)
+    lib().tri_oracle_unrotate_key(_ptr(key), _dtype_code(key), 0, key.shape[-1], pairs, float(theta), int(p_k), _ptr(out))
+    return out
+
+
+def raw_scores(stats, K, pos, cur_pos, theta, offsets, pairs=PAIR_INTERLEAVED, threads=1, variant=VARIANT_FULL,
+               rotated=False):
     """stats [G][F][3], K [N][d], pos [N] -> raw [G][N] float64.
+
+    variant: one of the VARIANT_* scoring variants; rotated: K holds post-RoPE keys.
 
     threads > 1 only splits the keys into row ranges handed to a thread pool; every key is
     still scored by the same C routine, independently of the others."""
@@ -139,8 +163,13 @@ def raw_scores(stats, K, pos, cur_pos, theta, offsets, pairs=PAIR_INTERLEAVED, t
     def run(n0, n1):
         part = np.empty((G, n1 - n0), dtype=np.float64)
         Kc, pc = K[n0:n1], pos[n0:n1]
-        rc = L.tri_oracle_raw_scores(_ptr(stats), G, _ptr(Kc), _dtype_code(K), d, _ptr(pc), n1 - n0,
-                                     int(cur_pos), d, pairs, float(theta), _ptr(off), len(off), _ptr(part))
+        if variant == VARIANT_FULL and not rotated:
+            rc = L.tri_oracle_raw_scores(_ptr(stats), G, _ptr(Kc), _dtype_code(K), d, _ptr(pc), n1 - n0,
+                                         int(cur_pos), d, pairs, float(theta), _ptr(off), len(off), _ptr(part))
+        else:
+            rc = L.tri_oracle_raw_scores_ex(_ptr(stats), G, _ptr(Kc), _dtype_code(K), d, _ptr(pc), n1 - n0,
+                                            int(cur_pos), d, pairs, float(theta), _ptr(off), len(off), int(variant),
+                                            int(bool(rotated)), _ptr(part))
         assert rc == 0
         return part
 
@@ -218,9 +247,10 @@ def paged_compact(pool, row_elems, block_table, block_size, strides, layer, seq,
     assert rc == 0
 
 
-def head_instance(stats, K, pos, cur_pos, theta, offsets, B, pairs=PAIR_INTERLEAVED, threads=1):
+def head_instance(stats, K, pos, cur_pos, theta, offsets, B, pairs=PAIR_INTERLEAVED, threads=1, variant=VARIANT_FULL,
+                  rotated=False):
     """The whole step for one head-instance: raw scores, final scores, kept indices."""
-    raw = raw_scores(stats, K, pos, cur_pos, theta, offsets, pairs, threads=threads)
+    raw = raw_scores(stats, K, pos, cur_pos, theta, offsets, pairs, threads=threads, variant=variant, rotated=rotated)
     mu, sigma, final = gqa_final(raw)
     idx = topk(final, B)
     return dict(raw=raw, mu=mu, sigma=sigma, final=final, idx=idx)

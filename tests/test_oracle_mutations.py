@@ -25,6 +25,11 @@ MUTATIONS = [
     ("sum instead of mean over offsets", "return acc / (double)n_off;", "return acc;"),
     ("imaginary part from the wrong element", "first + 2 * (int64_t)f + 1);", "first + 2 * (int64_t)f);"),
     ("centre modulus mean dropped", "sabs += hypot(re, im);", "sabs += fabs(re);"),
+    ("un-rotation by the wrong sign", "double ki = -s * xr + c * xi;", "double ki = s * xr + c * xi;"),
+    ("un-rotation not applied", "kd = ORACLE_F64;\n            first = 0;", "kd = ORACLE_F64;\n            first = 0;\n            for (int e = 0; e < d; ++e) tmp[e] = load_elem(K, dtype, n * row_stride + e);"),
+    ("w/o R keeps the weighted term", "if (variant == 0 || variant == 2) S += tri_oracle_s_norm(", "if (variant != 1) S += tri_oracle_s_norm("),
+    ("trig-only keeps the norm term", "if (variant == 3) S += tri_oracle_s_norm0(", "if (variant == 3 || variant == 1) S += tri_oracle_s_norm0("),
+    ("unweighted norm uses the centre modulus", "s += qabs * hypot(kre, kim);", "s += hypot((double)stats[3 * f], (double)stats[3 * f + 1]) * hypot(kre, kim);"),
     ("compaction source off by one", "(int64_t)idx[j] * src_stride_bytes", "(int64_t)(idx[j] + 1) * src_stride_bytes"),
 ]
 

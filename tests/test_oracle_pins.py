@@ -386,3 +386,88 @@ def test_compact_fill_moves_only_into_holes(oracle):
         # pairing rule: i-th hole (ascending) <- i-th tail survivor (ascending)
         hole_slots = np.setdiff1d(np.arange(cnt), stay)
         np.testing.assert_array_equal(out[hole_slots], src[idx[idx >= cnt]])
+
+
+# ---- scoring variants of the ablation study, post-RoPE caches -----------------------------------
+
+def test_unweighted_norm_score(oracle):
+    """P16: S_norm^(0) = sum_f E|q_f| |k_f| (Section 4.1).  For a key that coincides with the query centre,
+    S_trig at distance 0 is sum_f |E q_f|^2 (a plain dot product of the centre with itself), and that is exactly
+    what the concentration weighting removes: S_norm^(0) - S_norm = sum_f |E q_f| |k_f|."""
+    rng = np.random.default_rng(41)
+    stats, key = random_case(rng, 64)
+    k = key[0::2].astype(np.float64) + 1j * key[1::2].astype(np.float64)
+    assert oracle.s_norm0(stats, key) == pytest.approx(float(np.sum(stats[:, 2].astype(np.float64) * np.abs(k))), rel=1e-12)
+    centre_key = stats[:, 0:2].reshape(-1).copy()
+    dot = float(np.dot(centre_key.astype(np.float64), centre_key.astype(np.float64)))
+    assert oracle.s_trig(stats, centre_key, 1e4, 0) == pytest.approx(dot, rel=1e-12)
+    assert oracle.s_norm0(stats, centre_key) - oracle.s_norm(stats, centre_key) == pytest.approx(dot, rel=1e-9)
+    # half-split layout reads the same numbers from other places
+    perm = np.concatenate([key[0::2], key[1::2]])
+    assert oracle.s_norm0(stats, perm, pairs=oracle.PAIR_HALF) == oracle.s_norm0(stats, key)
+
+
+def test_variants_are_the_sums_of_their_parts(oracle):
+    """P17: the ablation variants (Section 5): trig-only + norm-only = full; "w/o R" exceeds the full score by
+    S_norm^(0) - S_norm; norm-only does not depend on positions or offsets; trig-only of a single offset is one
+    evaluation of the series."""
+    rng = np.random.default_rng(42)
+    G, N, d = 3, 40, 32
+    stats = np.stack([random_case(rng, d)[0] for _ in range(G)])
+    K = (rng.standard_normal((N, d)) * 2).astype(np.float32)
+    pos = np.sort(rng.choice(500, size=N, replace=False)).astype(np.int32)
+    offs = [1, 2, 4, 8, 16]
+    full = oracle.raw_scores(stats, K, pos, 600, 1e4, offs)
+    trig = oracle.raw_scores(stats, K, pos, 600, 1e4, offs, variant=oracle.VARIANT_TRIG_ONLY)
+    norm = oracle.raw_scores(stats, K, pos, 600, 1e4, offs, variant=oracle.VARIANT_NORM_ONLY)
+    unw = oracle.raw_scores(stats, K, pos, 600, 1e4, offs, variant=oracle.VARIANT_NORM_UNWEIGHTED)
+    np.testing.assert_allclose(trig + norm, full, rtol=1e-12, atol=1e-12)
+    for g in range(G):
+        for n in range(N):
+            assert norm[g, n] == pytest.approx(oracle.s_norm(stats[g], K[n]), rel=1e-13)
+            extra = oracle.s_norm0(stats[g], K[n]) - oracle.s_norm(stats[g], K[n])
+            assert unw[g, n] - full[g, n] == pytest.approx(extra, rel=1e-9, abs=1e-9)
+    norm2 = oracle.raw_scores(stats, K, pos[::-1].copy(), 99999, 1e4, [3], variant=oracle.VARIANT_NORM_ONLY)
+    np.testing.assert_allclose(norm2, norm, rtol=1e-13)
+    one = oracle.raw_scores(stats, K, pos, 600, 1e4, [7], variant=oracle.VARIANT_TRIG_ONLY)
+    for n in range(0, N, 7):
+        assert one[1, n] == pytest.approx(oracle.s_trig(stats[1], K[n], 1e4, 600 - int(pos[n]) + 7), rel=1e-12, abs=1e-12)
+
+
+@pytest.mark.parametrize("pairs", [0, 1])
+def test_post_rope_cache(oracle, pairs):
+    """P18: a cache that stores R(p_k) k (Section 2.1 Eq. 1).  Un-rotating what the 2x2 matrices produced gives the
+    key back; the scores of the rotated cache equal those of the pre-RoPE cache; and S_trig is then the plain dot
+    product of the stored key with the centre rotated to the query position (the post-RoPE attention logit)."""
+    rng = np.random.default_rng(43 + pairs)
+    G, N, d, theta = 2, 25, 64, 1e4
+    stats = np.stack([random_case(rng, d)[0] for _ in range(G)])
+    K = (rng.standard_normal((N, d)) * 2).astype(np.float64)      # interleaved pre-RoPE keys
+    pos = rng.integers(0, 3000, size=N).astype(np.int32)
+    Krot = np.stack([rope_rotate(K[n], int(pos[n]), theta) for n in range(N)])
+
+    def store(x):   # interleaved -> the layout under test, rounded to the float32 storage type
+        x = np.concatenate([x[..., 0::2], x[..., 1::2]], axis=-1) if pairs else x
+        return np.ascontiguousarray(x.astype(np.float32))
+
+    K32, Krot32 = store(K), store(Krot)
+    for n in range(0, N, 6):
+        back = oracle.unrotate_key(Krot32[n], theta, int(pos[n]), pairs=pairs)
+        np.testing.assert_allclose(back, K32[n].astype(np.float64), atol=2e-6)
+    offs = [1, 4, 16]
+    a = oracle.raw_scores(stats, K32, pos, 3100, theta, offs, pairs=pairs)
+    b = oracle.raw_scores(stats, Krot32, pos, 3100, theta, offs, pairs=pairs, rotated=True)
+    np.testing.assert_allclose(b, a, rtol=0, atol=1e-4)   # float32 rounding of the stored rotated key
+    assert np.abs(a).max() > 1.0
+    # un-rotation matters: reading the rotated cache as if it were pre-RoPE gives other scores
+    c = oracle.raw_scores(stats, Krot32, pos, 3100, theta, offs, pairs=pairs)
+    assert np.abs(c - a).max() > 0.1
+    # single offset 0, trig only: the logit of the rotated centre with the stored key
+    t = oracle.raw_scores(stats, Krot32, pos, 3100, theta, [0], pairs=pairs, rotated=True, variant=oracle.VARIANT_TRIG_ONLY)
+    for n in range(0, N, 5):
+        centre = stats[0][:, 0:2].reshape(-1).astype(np.float64)
+        stored = Krot32[n].astype(np.float64)
+        if pairs:
+            stored = np.stack([stored[: d // 2], stored[d // 2:]], axis=-1).reshape(-1)
+        brute = float(np.dot(rope_rotate(centre, 3100, theta), stored))
+        assert t[0, n] == pytest.approx(brute, rel=1e-9, abs=1e-9)
