@@ -52,6 +52,15 @@ typedef enum {
     TRI_PAIR_HALF = 1         /* (x[f], x[f + head_dim/2]) -- half-split checkpoints  */
 } tri_pair_layout;
 
+/* which components the score is made of: the method, and the variants its ablation study removes a
+ * component from (Section 5, ablations of the scoring components and of the adaptive weighting) */
+typedef enum {
+    TRI_SCORE_FULL = 0,           /* S_trig + S_norm (Sections 4.1-4.2)                          */
+    TRI_SCORE_TRIG_ONLY = 1,      /* S_trig alone ("w/o S_norm")                                  */
+    TRI_SCORE_NORM_ONLY = 2,      /* S_norm alone ("w/o S_trig")                                  */
+    TRI_SCORE_NORM_UNWEIGHTED = 3 /* S_trig + S_norm^(0) = sum_f E||q_f|| ||k_f|| ("w/o R")       */
+} tri_score_variant;
+
 /* Model geometry and the scoring hyper-parameters (Section 2.1: omega_f = theta^(-2f/d);
  * Section 4.2: the offset set D, geometric in the paper). */
 typedef struct tri_model {
@@ -63,10 +72,11 @@ typedef struct tri_model {
     int32_t pairs;          /* tri_pair_layout */
     int32_t n_offsets;      /* |D| >= 1 */
     const int64_t *offsets; /* HOST array [n_offsets] */
+    int32_t score_variant;  /* tri_score_variant; 0 = the method */
 } tri_model;
 
 /*
- * A KV cache holding pre-RoPE keys, values and key positions for n_layers x n_seqs x n_kv_heads
+ * A KV cache holding keys (pre-RoPE, or post-RoPE with k_rotated), values and key positions for n_layers x n_seqs x n_kv_heads
  * head-instances.  One descriptor covers both layouts:
  *   contiguous (block_size == 0): slot n of (layer l, sequence s, head h) is at element
  *       l*stride_layer + s*stride_seq_or_block + h*stride_head + n*stride_slot
@@ -90,6 +100,10 @@ typedef struct tri_cache {
     int32_t max_blocks_per_seq;
     int64_t stride_layer, stride_seq_or_block, stride_head, stride_slot;
     int64_t pos_stride_layer, pos_stride_seq_or_block, pos_stride_head;
+    int32_t k_rotated;            /* 0: k holds pre-RoPE keys (the paper's setting).  1: k holds post-RoPE keys,
+                                     each already rotated by its own position (Section 2.1 Eq. 1), as serving
+                                     stacks usually store them; the scores are the same, the rotation of the key
+                                     in the score kernel is skipped and pos is read by tri_compact only */
 } tri_cache;
 
 const char *tri_last_error(void);

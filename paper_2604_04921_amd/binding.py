@@ -15,6 +15,7 @@ TRI_OK = 0
 TRI_ERR_INVALID_ARG, TRI_ERR_UNSUPPORTED, TRI_ERR_WORKSPACE, TRI_ERR_HIP = -1, -2, -3, -4
 TRI_F32, TRI_BF16 = 0, 1
 TRI_PAIR_INTERLEAVED, TRI_PAIR_HALF = 0, 1
+TRI_SCORE_FULL, TRI_SCORE_TRIG_ONLY, TRI_SCORE_NORM_ONLY, TRI_SCORE_NORM_UNWEIGHTED = 0, 1, 2, 3
 
 EXPORTS = ["tri_last_error", "tri_build_centers", "tri_workspace_size", "tri_score", "tri_select_topk",
            "tri_compact", "tri_compact_fill", "tri_compress_step", "tri_timing_attach", "tri_timing_detach"]
@@ -23,7 +24,7 @@ EXPORTS = ["tri_last_error", "tri_build_centers", "tri_workspace_size", "tri_sco
 class TriModel(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("rope_theta", ctypes.c_double), ("pairs", ctypes.c_int32),
-                ("n_offsets", ctypes.c_int32), ("offsets", ctypes.c_void_p)]
+                ("n_offsets", ctypes.c_int32), ("offsets", ctypes.c_void_p), ("score_variant", ctypes.c_int32)]
 
 
 class TriCache(ctypes.Structure):
@@ -35,7 +36,7 @@ class TriCache(ctypes.Structure):
                 ("stride_layer", ctypes.c_int64), ("stride_seq_or_block", ctypes.c_int64),
                 ("stride_head", ctypes.c_int64), ("stride_slot", ctypes.c_int64),
                 ("pos_stride_layer", ctypes.c_int64), ("pos_stride_seq_or_block", ctypes.c_int64),
-                ("pos_stride_head", ctypes.c_int64)]
+                ("pos_stride_head", ctypes.c_int64), ("k_rotated", ctypes.c_int32)]
 
 
 class TriError(RuntimeError):
@@ -108,10 +109,11 @@ def _dtype(t):
 class Model:
     """Host-side tri_model; keeps the offsets array alive."""
 
-    def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, rope_theta, offsets, pairs=TRI_PAIR_INTERLEAVED):
+    def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, rope_theta, offsets, pairs=TRI_PAIR_INTERLEAVED,
+                 score_variant=TRI_SCORE_FULL):
         self._offsets = np.ascontiguousarray(offsets, dtype=np.int64)
         self.c = TriModel(n_layers, n_q_heads, n_kv_heads, head_dim, float(rope_theta), pairs, len(self._offsets),
-                          self._offsets.ctypes.data_as(ctypes.c_void_p))
+                          self._offsets.ctypes.data_as(ctypes.c_void_p), int(score_variant))
 
     @property
     def ref(self):
@@ -125,7 +127,7 @@ class Cache:
     paged:      k, v [L][n_blocks][Hkv][block][d], pos [L][n_blocks][Hkv][block], block_table [S][max_blocks]
     Strides are taken from the tensors; the last dimension must be dense."""
 
-    def __init__(self, k, v, pos, seq_len, cur_pos, max_seq_len, block_table=None):
+    def __init__(self, k, v, pos, seq_len, cur_pos, max_seq_len, block_table=None, k_rotated=False):
         assert k.dim() == 5 and pos.dim() == 4 and k.stride(4) == 1 and pos.stride(3) == 1
         assert v is None or (v.stride() == k.stride() and v.dtype == k.dtype)
         assert pos.dtype == torch.int32 and seq_len.dtype == torch.int32 and cur_pos.dtype == torch.int32
@@ -136,7 +138,7 @@ class Cache:
                           0 if block_table is None else block_table.data_ptr(),
                           0 if block_table is None else block_table.shape[1],
                           k.stride(0), k.stride(1), k.stride(2), k.stride(3),
-                          pos.stride(0), pos.stride(1), pos.stride(2))
+                          pos.stride(0), pos.stride(1), pos.stride(2), int(bool(k_rotated)))
         if block_table is not None:
             assert block_table.dtype == torch.int32 and block_table.is_contiguous()
 

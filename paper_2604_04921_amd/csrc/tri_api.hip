@@ -63,6 +63,10 @@ tri_status check_model(const tri_model *m)
         set_error("unknown pair layout %d", m->pairs);
         return TRI_ERR_INVALID_ARG;
     }
+    if (m->score_variant < TRI_SCORE_FULL || m->score_variant > TRI_SCORE_NORM_UNWEIGHTED) {
+        set_error("unknown score variant %d", m->score_variant);
+        return TRI_ERR_INVALID_ARG;
+    }
     if (m->n_offsets < 1 || m->n_offsets > kMaxOffsets || !m->offsets) {
         set_error("n_offsets must be in [1, %d] with a host offsets array", kMaxOffsets);
         return TRI_ERR_INVALID_ARG;
@@ -142,6 +146,7 @@ CacheView make_view(const tri_model &m, const tri_cache &c)
         while ((1 << v.block_shift) < c.block_size) ++v.block_shift;
     }
     v.max_blocks = c.max_blocks_per_seq;
+    v.k_rotated = c.k_rotated != 0;
     return v;
 }
 

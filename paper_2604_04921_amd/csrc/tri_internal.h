@@ -29,6 +29,7 @@ struct CacheView {
     int32_t max_seq_len;
     int32_t block_shift;   // log2(block_size), -1 = contiguous
     int32_t max_blocks;
+    int32_t k_rotated;     // keys stored post-RoPE: no rotation in the score kernel
 };
 
 // Element offset of slot n of (layer, seq, head) in k / v.

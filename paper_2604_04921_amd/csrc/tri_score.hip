@@ -25,6 +25,7 @@ struct FoldArgs {
     int32_t S, Hq, Hkv, G;
     double theta;
     int32_t n_off;
+    int32_t variant;        // tri_score_variant
     int64_t offsets[kMaxOffsets];
 };
 
@@ -54,8 +55,11 @@ __global__ __launch_bounds__(kBands) void fold_kernel(FoldArgs a)
     ei /= (double)a.n_off;
     const float *ct = a.centers + (((int64_t)l * a.Hq + qh) * kBands + f) * 3;
     const double qr = (double)ct[0], qi = (double)ct[1], qa = (double)ct[2];
-    const double ar = qr * er - qi * ei, ai = qr * ei + qi * er;
-    const double cn = qa - hypot(qr, qi);
+    // the ablation variants (Section 5) only change the table: no trig part, no norm part, or the norm
+    // part without its (1 - R_f) weight, i.e. S_norm^(0) of Section 4.1
+    const bool trig_on = a.variant != TRI_SCORE_NORM_ONLY, norm_on = a.variant != TRI_SCORE_TRIG_ONLY;
+    const double ar = trig_on ? qr * er - qi * ei : 0.0, ai = trig_on ? qr * ei + qi * er : 0.0;
+    const double cn = !norm_on ? 0.0 : a.variant == TRI_SCORE_NORM_UNWEIGHTED ? qa : qa - hypot(qr, qi);
     const int h = qh / a.G, g = qh % a.G;
     for (int s = 0; s < a.S; ++s) {
         double c, sn;
@@ -120,7 +124,7 @@ __global__ __launch_bounds__(kScoreTile) void score_kernel(ScoreArgs a)
 
     row_off[tid] = valid ? kv_offset(c, l, s, h, n) : (int64_t)-1;
     int p = 0;
-    if (valid) p = c.pos[pos_offset(c, l, s, h, n)];
+    if (valid && !c.k_rotated) p = c.pos[pos_offset(c, l, s, h, n)];   // a post-RoPE key needs no rotation
     __syncthreads();
 
     const T *kbase = (const T *)c.k;
@@ -377,6 +381,7 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     fo.G = G;
     fo.theta = m.rope_theta;
     fo.n_off = m.n_offsets;
+    fo.variant = m.score_variant;
     for (int j = 0; j < m.n_offsets; ++j) fo.offsets[j] = m.offsets[j];
     hipLaunchKernelGGL(fold_kernel, dim3(m.n_q_heads, m.n_layers), dim3(kBands), 0, st, fo);
     tri_status rc = hip_status("fold_kernel");

@@ -91,7 +91,8 @@ __device__ __forceinline__ uint4 load_stream16(const char *p)
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-template <int NG>
+// ROTATE = false: the key is stored post-RoPE, already k e^{i w p}
+template <int NG, bool ROTATE = true>
 __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4], const float (&sn)[4],
                                            const LaneTable (&tb)[NG], float (&out)[NG])
 {
@@ -102,8 +103,8 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const float re = bf16_lo(w[k]), im = bf16_hi(w[k]);
-        const float kr = re * cs[k] - im * sn[k];
-        const float ki = re * sn[k] + im * cs[k];
+        const float kr = ROTATE ? re * cs[k] - im * sn[k] : re;
+        const float ki = ROTATE ? re * sn[k] + im * cs[k] : im;
         // |k_f|^2 straight from the packed bf16 pair (products of bf16 are exact in fp32)
         const bf16x2 kk = __builtin_bit_cast(bf16x2, w[k]);
         const float m = __builtin_amdgcn_sqrtf(__builtin_amdgcn_fdot2_f32_bf16(kk, kk, 0.0f, false));
@@ -121,7 +122,7 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
 // grid (ceil(Nmax / kFastChunk), S*Hkv, L), block 512.  The workgroup's keys (8192, fewer in the last
 // chunk of a sequence) are split evenly over its 8 waves; each wave walks its contiguous share in
 // groups of 16 (4 steps).  PAGED: block_size >= 16, so a group never straddles a block.
-template <int G, bool PAGED>
+template <int G, bool PAGED, bool ROTATED>
 __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 {
     constexpr int NG = (G + 3) / 4;
@@ -141,7 +142,8 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     if (chunk * kFastChunk >= N) return;   // uniform over the workgroup
 
     const int64_t inst = ((int64_t)l * c.n_seqs + s) * c.n_kv_heads + h;
-    for (int k = tid; k < kPhasorBytes / 16; k += kFastThreads) lds_phasors[k] = a.phasors[k];
+    if constexpr (!ROTATED)
+        for (int k = tid; k < kPhasorBytes / 16; k += kFastThreads) lds_phasors[k] = a.phasors[k];
     for (int k = tid; k < kBands * 3 * G; k += kFastThreads) lds_tab[k] = a.table[inst * (kBands * 3 * G) + k];
     if (tid < kBands) lds_rev[tid] = a.band_rev[tid];
     __syncthreads();
@@ -215,7 +217,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
         group_ptrs(n, kp, pq);
 #pragma unroll
         for (int t = 0; t < 4; ++t) kd[t] = load_stream16(kp + koff[t]);
-        pp = pq[ld_piece];
+        pp = ROTATED ? 0 : pq[ld_piece];
     };
 
     // last, partial group: keys past the end repeat the last one (their results are discarded)
@@ -228,7 +230,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
             const int j = min(4 * t + ld_key, cnt - 1);
             kd[t] = load_stream16(kp + (uint32_t)j * slot_bytes + (uint32_t)ld_piece * 16u);
         }
-        pp = pq[min(ld_piece, cnt - 1)];
+        pp = ROTATED ? 0 : pq[min(ld_piece, cnt - 1)];
     };
 
     // load order -> consumer order
@@ -302,42 +304,53 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             kd[t] = to_consumer(kraw[t]);
-            pp[t] = __builtin_amdgcn_ds_bpermute(perm_p + 16 * t, praw);
+            pp[t] = ROTATED ? 0 : __builtin_amdgcn_ds_bpermute(perm_p + 16 * t, praw);
         }
         float kept[NG];
 #pragma unroll
         for (int q = 0; q < NG; ++q) kept[q] = 0.f;
-        // common case: all 16 positions of the group fall in the table around the current base
-        const unsigned far = max(max((unsigned)(pp[0] - base), (unsigned)(pp[1] - base)),
-                                 max((unsigned)(pp[2] - base), (unsigned)(pp[3] - base)));
-        bool fast = __builtin_amdgcn_ballot_w64(far >= (unsigned)kPhasorRange) == 0ull;
-        if (!fast) {
-            // span of the 16 positions (lanes 0..3 hold four each)
-            int lo = min(min(pp[0], pp[1]), min(pp[2], pp[3])), hi = max(max(pp[0], pp[1]), max(pp[2], pp[3]));
-            lo = min(min(__builtin_amdgcn_readlane(lo, 0), __builtin_amdgcn_readlane(lo, 1)),
-                     min(__builtin_amdgcn_readlane(lo, 2), __builtin_amdgcn_readlane(lo, 3)));
-            hi = max(max(__builtin_amdgcn_readlane(hi, 0), __builtin_amdgcn_readlane(hi, 1)),
-                     max(__builtin_amdgcn_readlane(hi, 2), __builtin_amdgcn_readlane(hi, 3)));
-            if ((int64_t)hi - (int64_t)lo < kPhasorRange) {
-                move_base(lo);
-                fast = true;
-            }
-        }
-        if (fast) {
-            float out[4][NG];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) step_table(kd[t], pp[t] - base, out[t]);
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[t][q] : kept[q];
-        } else {
+        if constexpr (ROTATED) {   // post-RoPE keys: straight into the contraction
+            const float one[4] = {1.f, 1.f, 1.f, 1.f}, zero[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 float out[NG];
-                step_general(kd[t], pp[t], out);
+                score_step<NG, false>(kd[t], one, zero, tb, out);
 #pragma unroll
                 for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
+            }
+        } else {
+            // common case: all 16 positions of the group fall in the table around the current base
+            const unsigned far = max(max((unsigned)(pp[0] - base), (unsigned)(pp[1] - base)),
+                                     max((unsigned)(pp[2] - base), (unsigned)(pp[3] - base)));
+            bool fast = __builtin_amdgcn_ballot_w64(far >= (unsigned)kPhasorRange) == 0ull;
+            if (!fast) {
+                // span of the 16 positions (lanes 0..3 hold four each)
+                int lo = min(min(pp[0], pp[1]), min(pp[2], pp[3])), hi = max(max(pp[0], pp[1]), max(pp[2], pp[3]));
+                lo = min(min(__builtin_amdgcn_readlane(lo, 0), __builtin_amdgcn_readlane(lo, 1)),
+                         min(__builtin_amdgcn_readlane(lo, 2), __builtin_amdgcn_readlane(lo, 3)));
+                hi = max(max(__builtin_amdgcn_readlane(hi, 0), __builtin_amdgcn_readlane(hi, 1)),
+                         max(__builtin_amdgcn_readlane(hi, 2), __builtin_amdgcn_readlane(hi, 3)));
+                if ((int64_t)hi - (int64_t)lo < kPhasorRange) {
+                    move_base(lo);
+                    fast = true;
+                }
+            }
+            if (fast) {
+                float out[4][NG];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) step_table(kd[t], pp[t] - base, out[t]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[t][q] : kept[q];
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    float out[NG];
+                    step_general(kd[t], pp[t], out);
+#pragma unroll
+                    for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
+                }
             }
         }
         // lane (row, sub, j) now holds key n + 4*sub + row for head j (+4q): 16 keys x 4 heads per wave
@@ -407,11 +420,14 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 template <int G>
 tri_status launch_fast_g(const ScoreArgs &sa, int n_layers, hipStream_t st)
 {
-    auto kern = sa.c.block_shift >= 0 ? score_mfma_kernel<G, true> : score_mfma_kernel<G, false>;
-    if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kPhasorBytes) != hipSuccess)
+    const bool paged = sa.c.block_shift >= 0;
+    auto kern = sa.c.k_rotated ? (paged ? score_mfma_kernel<G, true, true> : score_mfma_kernel<G, false, true>)
+                               : (paged ? score_mfma_kernel<G, true, false> : score_mfma_kernel<G, false, false>);
+    const int lds = sa.c.k_rotated ? 0 : kPhasorBytes;   // no phasor table for post-RoPE keys
+    if (lds && hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return hip_status("hipFuncSetAttribute(score_mfma_kernel)");
     dim3 grid(sa.n_tiles, sa.c.n_seqs * sa.c.n_kv_heads, n_layers);
-    hipLaunchKernelGGL(kern, grid, dim3(kFastThreads), kPhasorBytes, st, sa);
+    hipLaunchKernelGGL(kern, grid, dim3(kFastThreads), lds, st, sa);
     return hip_status("score_mfma_kernel");
 }
 

@@ -10,19 +10,20 @@ import tri_harness as H
 pytestmark = pytest.mark.gpu
 
 
-def oracle_instance(oracle, cfg, w, stats, l, s, h, threads=8, pairs=0):
+def oracle_instance(oracle, cfg, w, stats, l, s, h, threads=8, pairs=0, variant=0, rotated=False):
     G = cfg.group
     n = int(w["seq_len"][s])
     return oracle.head_instance(stats[l, h * G:(h + 1) * G], w["k"][l, s, h, :n], w["pos"][l, s, h, :n],
                                 int(w["cur_pos"][s]), cfg.rope_theta, cfg.offsets, cfg.budget, pairs=pairs,
-                                threads=threads)
+                                threads=threads, variant=variant, rotated=rotated)
 
 
-def run_and_check(oracle, cfg, instances=None, paged=False, inplace=False, pairs=0, mutate=None):
+def run_and_check(oracle, cfg, instances=None, paged=False, inplace=False, pairs=0, mutate=None, variant=0,
+                  rotated=False):
     w = recipe.generate(cfg)
     if mutate is not None:
         mutate(w)
-    run = H.GpuRun(cfg, w, paged=paged, pairs=pairs)
+    run = H.GpuRun(cfg, w, paged=paged, pairs=pairs, variant=variant, rotated=rotated)
     stats_gpu = run.build_centers()
     stats = oracle.centers(w["q_samples"], pairs=pairs)
     np.testing.assert_allclose(stats_gpu, stats, rtol=3e-7, atol=1e-30)
@@ -40,7 +41,7 @@ def run_and_check(oracle, cfg, instances=None, paged=False, inplace=False, pairs
         if n == 0:
             assert cnt[l, s, h] == 0
             continue
-        ref = oracle_instance(oracle, cfg, w, stats, l, s, h, pairs=pairs)
+        ref = oracle_instance(oracle, cfg, w, stats, l, s, h, pairs=pairs, variant=variant, rotated=rotated)
         worst_raw = max(worst_raw, H.check_raw(raw[l, s, h * G:(h + 1) * G, :n], ref["raw"]))
         worst_final = max(worst_final, H.check_final(final[l, s, h, :n], ref["final"]))
         exact += H.check_kept(idx[l, s, h], int(cnt[l, s, h]), ref["final"], ref["idx"], n, cfg.budget)
@@ -141,3 +142,29 @@ def test_half_split_pairs(oracle):
             w[name] = np.ascontiguousarray(np.concatenate([x[..., 0::2], x[..., 1::2]], axis=-1))
 
     run_and_check(oracle, cfg, pairs=1, mutate=mutate)
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_score_variants(oracle, variant, dtype):
+    """The ablation variants (trig only, norm only, un-weighted norm) on the MFMA kernel (bf16) and the generic one."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=2, n_q_heads=8, n_kv_heads=2, seq_len=700,
+                        min_seq_len=300, budget=96, n_calib=128, dtype=dtype)
+    run_and_check(oracle, cfg, variant=variant)
+
+
+@pytest.mark.parametrize("dtype,pairs,paged", [("bf16", 0, False), ("bf16", 0, True), ("bf16", 1, False), ("f32", 0, False)])
+def test_post_rope_cache(oracle, dtype, pairs, paged):
+    """A cache of post-RoPE keys (every key rotated by its own position before it was stored)."""
+    base = recipe.CONFIGS["c4_paged" if paged else "c2_layer"]
+    cfg = recipe.scaled(base, n_layers=2, n_seqs=2, n_q_heads=8, n_kv_heads=2, seq_len=800, min_seq_len=200,
+                        budget=128, n_calib=128, dtype=dtype)
+
+    def mutate(w):
+        if pairs:
+            for name in ("k", "q_samples"):
+                x = w[name]
+                w[name] = np.ascontiguousarray(np.concatenate([x[..., 0::2], x[..., 1::2]], axis=-1))
+        w["k"] = recipe.to_post_rope(w["k"], w["pos"], cfg.rope_theta, pairs, cfg.dtype)
+
+    run_and_check(oracle, cfg, paged=paged, pairs=pairs, mutate=mutate, rotated=True)

@@ -27,13 +27,13 @@ def to_numpy(t):
 class GpuRun:
     """One workload resident on the GPU with the buffers the four entry points need."""
 
-    def __init__(self, cfg, w, paged=False, pairs=0):
+    def __init__(self, cfg, w, paged=False, pairs=0, variant=0, rotated=False):
         from paper_2604_04921_amd import binding as B
         self.B = B
         self.cfg = cfg
         dev = "cuda"
         self.model = B.Model(cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rope_theta, cfg.offsets,
-                             pairs)
+                             pairs, variant)
         self.q = to_torch(w["q_samples"], cfg.dtype)
         self.seq_len = torch.from_numpy(w["seq_len"]).to(dev)
         self.cur_pos = torch.from_numpy(w["cur_pos"]).to(dev)
@@ -50,7 +50,8 @@ class GpuRun:
             self.v = to_torch(w["v"], cfg.dtype)
             self.pos = torch.from_numpy(w["pos"]).to(dev)
         self.nmax = int(cfg.seq_len)
-        self.cache = B.Cache(self.k, self.v, self.pos, self.seq_len, self.cur_pos, self.nmax, self.block_table)
+        self.cache = B.Cache(self.k, self.v, self.pos, self.seq_len, self.cur_pos, self.nmax, self.block_table,
+                             k_rotated=rotated)
         L, S, Hq, Hkv = cfg.n_layers, cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads
         self.centers = torch.empty((L, Hq, cfg.n_bands, 3), dtype=torch.float32, device=dev)
         self.final = torch.full((L, S, Hkv, self.nmax), float("nan"), dtype=torch.float32, device=dev)
