@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--split", action="store_true", help="call the three entry points instead of the fused one")
     ap.add_argument("--fill", action="store_true",
                     help="evict in place with the fewest moves (tri_compact_fill) instead of the ordered compaction")
+    ap.add_argument("--post-rope", action="store_true", help="treat the cache as holding post-RoPE keys (k_rotated)")
+    ap.add_argument("--half-split", action="store_true", help="band f = (x[f], x[f + d/2]) instead of (x[2f], x[2f+1])")
+    ap.add_argument("--variant", type=int, default=0, help="score variant (0 full, 1 trig only, 2 norm only, 3 un-weighted norm)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic for scaling rocprofv3 byte counters)")
     ap.add_argument("--hbm-probe", action="store_true",
@@ -65,8 +68,9 @@ def main():
     t_gen = time.time()
     w = device.generate(cfg, positions=mode, layers=L)
     S, Hq, Hkv, B, d = cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads, cfg.budget, cfg.head_dim
-    model = T.Model(L, Hq, Hkv, d, cfg.rope_theta, cfg.offsets)
-    src = T.Cache(w["k"], w["v"], w["pos"], w["seq_len"], w["cur_pos"], cfg.seq_len, w.get("block_table"))
+    model = T.Model(L, Hq, Hkv, d, cfg.rope_theta, cfg.offsets, pairs=int(args.half_split), score_variant=args.variant)
+    src = T.Cache(w["k"], w["v"], w["pos"], w["seq_len"], w["cur_pos"], cfg.seq_len, w.get("block_table"),
+                  k_rotated=args.post_rope)
     centers = torch.empty((L, Hq, d // 2, 3), dtype=torch.float32, device=dev)
     T.tri_build_centers(model, w["q_samples"], centers)
     paged = "block_table" in w
@@ -154,7 +158,8 @@ def main():
 
     cpu = None
     if not args.no_cpu:
-        cpu = cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, args.cpu_instances, paged)
+        cpu = cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, args.cpu_instances, paged, args.variant, args.post_rope,
+                           int(args.half_split))
 
     out = {"metric": "cached keys scored+selected+compacted per second", "value": round(value, 3), "unit": "Gkeys/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
@@ -165,12 +170,13 @@ def main():
                       "n_offsets": cfg.n_offsets, "storage": cfg.dtype, "layout": "paged16" if paged else "contiguous",
                       "keys": keys, "entry": "split" if args.split else "tri_compress_step",
                       "compaction": "fill" if args.fill else "ordered",
+                      "keys_stored": "post-rope" if args.post_rope else "pre-rope", "score_variant": args.variant, "pairs": "half-split" if args.half_split else "interleaved",
                       "generate_s": round(t_gen, 1)},
            "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, n_inst, paged):
+def cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, n_inst, paged, variant=0, rotated=False, pairs=0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: whole head-instances spread
     over layers and sequences, copied back from the device.  Also confirms the GPU's kept sets on them."""
     import numpy as np
@@ -198,7 +204,8 @@ def cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, n_inst, paged):
         jobs.append((stats[l, h * G:(h + 1) * G], kn, p.cpu().numpy(), int(cur[s])))
     O.lib()
     t0 = time.perf_counter()
-    res = [O.head_instance(st, kn, p, c, cfg.rope_theta, cfg.offsets, cfg.budget, threads=threads)
+    res = [O.head_instance(st, kn, p, c, cfg.rope_theta, cfg.offsets, cfg.budget, threads=threads, variant=variant,
+                            rotated=rotated, pairs=pairs)
            for (st, kn, p, c) in jobs]
     dt = time.perf_counter() - t0
     nkeys = sum(j[1].shape[0] for j in jobs)

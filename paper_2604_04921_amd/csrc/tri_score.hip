@@ -333,9 +333,9 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
                           float *final_out, hipStream_t st)
 {
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
-    // MFMA kernel: bf16, interleaved pairs, a group of 16 slots never straddling a block, 32-bit row offsets
-    const bool fast = c.dtype == TRI_BF16 && m.pairs == TRI_PAIR_INTERLEAVED &&
-                      (c.block_size == 0 || c.block_size >= 16) && c.stride_slot * 2 * 16 < ((int64_t)1 << 31);
+    // MFMA kernel: bf16, a group of 16 slots never straddling a block, 32-bit row offsets
+    const bool fast = c.dtype == TRI_BF16 && (c.block_size == 0 || c.block_size >= 16) &&
+                      c.stride_slot * 2 * 16 < ((int64_t)1 << 31);
     const int tile_keys = fast ? kFastChunk : kScoreTile;
     sa.n_tiles = (c.max_seq_len + tile_keys - 1) / tile_keys;
     tri_status rc = TRI_OK;
@@ -344,7 +344,7 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
     const bool timed = timing_next(&ev0, &ev1);
     if (timed) (void)hipEventRecord(ev0, st);
     if (fast) {
-        rc = launch_score_fast(G, sa, m.n_layers, st);
+        rc = launch_score_fast(G, sa, m.n_layers, m.pairs == TRI_PAIR_HALF, st);
     } else {
         dim3 grid(sa.n_tiles, c.n_seqs * m.n_kv_heads, m.n_layers);
         rc = (c.dtype == TRI_BF16) ? launch_score_kernel<G, uint16_t>(m, sa, grid, st)

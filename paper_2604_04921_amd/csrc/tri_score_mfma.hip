@@ -1,4 +1,4 @@
-// Score kernel for bf16 keys with interleaved pairs: fp32 MFMA for the contraction over
+// Score kernel for bf16 keys (interleaved or half-split pairs): fp32 MFMA for the contraction over
 // (band, component) x query head, a phasor table in LDS for the rotation of the key.
 //
 // Lane layout (wave64): lane = 4*b + i.  In one step a wave scores 4 keys; lane (b, i) loads the
@@ -91,8 +91,10 @@ __device__ __forceinline__ uint4 load_stream16(const char *p)
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-// ROTATE = false: the key is stored post-RoPE, already k e^{i w p}
-template <int NG, bool ROTATE = true>
+// ROTATE = false: the key is stored post-RoPE, already k e^{i w p}.
+// HALF = false: kd holds the (re, im) pairs of the lane's four bands; HALF = true (half-split layout):
+// kd = (re of bands 0-1, re of bands 2-3, im of bands 0-1, im of bands 2-3), two bf16 per dword.
+template <int NG, bool ROTATE, bool HALF>
 __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4], const float (&sn)[4],
                                            const LaneTable (&tb)[NG], float (&out)[NG])
 {
@@ -102,12 +104,20 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
     for (int q = 0; q < NG; ++q) acc[q] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const float re = bf16_lo(w[k]), im = bf16_hi(w[k]);
+        float re, im, m;
+        if constexpr (HALF) {
+            re = (k & 1) ? bf16_hi(w[k >> 1]) : bf16_lo(w[k >> 1]);
+            im = (k & 1) ? bf16_hi(w[2 + (k >> 1)]) : bf16_lo(w[2 + (k >> 1)]);
+            m = __builtin_amdgcn_sqrtf(fmaf(re, re, im * im));
+        } else {
+            re = bf16_lo(w[k]);
+            im = bf16_hi(w[k]);
+            // |k_f|^2 straight from the packed bf16 pair (products of bf16 are exact in fp32)
+            const bf16x2 kk = __builtin_bit_cast(bf16x2, w[k]);
+            m = __builtin_amdgcn_sqrtf(__builtin_amdgcn_fdot2_f32_bf16(kk, kk, 0.0f, false));
+        }
         const float kr = ROTATE ? re * cs[k] - im * sn[k] : re;
         const float ki = ROTATE ? re * sn[k] + im * cs[k] : im;
-        // |k_f|^2 straight from the packed bf16 pair (products of bf16 are exact in fp32)
-        const bf16x2 kk = __builtin_bit_cast(bf16x2, w[k]);
-        const float m = __builtin_amdgcn_sqrtf(__builtin_amdgcn_fdot2_f32_bf16(kk, kk, 0.0f, false));
 #pragma unroll
         for (int q = 0; q < NG; ++q) {
             acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(kr, tb[q].rr[k], acc[q], 0, 0, 0);
@@ -122,7 +132,7 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
 // grid (ceil(Nmax / kFastChunk), S*Hkv, L), block 512.  The workgroup's keys (8192, fewer in the last
 // chunk of a sequence) are split evenly over its 8 waves; each wave walks its contiguous share in
 // groups of 16 (4 steps).  PAGED: block_size >= 16, so a group never straddles a block.
-template <int G, bool PAGED, bool ROTATED>
+template <int G, bool PAGED, bool ROTATED, bool HALF>
 __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 {
     constexpr int NG = (G + 3) / 4;
@@ -233,13 +243,32 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
         pp = ROTATED ? 0 : pq[min(ld_piece, cnt - 1)];
     };
 
+    // Half-split layout: a row is 64 real parts followed by 64 imaginary parts, so piece p < 8 holds the
+    // real parts of bands 8p..8p+7 and piece 8 + p their imaginary parts.  Consumer (b, i) needs dwords
+    // 2(b&1), 2(b&1)+1 of pieces b>>1 and 8 + (b>>1) of key i.  Four permutes still do: in each, the real
+    // pieces offer one dword and the imaginary pieces another, and even / odd consumers read opposite kinds.
+    const bool ld_im = ld_piece >= 8, odd_b = (b & 1) != 0;
+    const int perm_re = (16 * i + (b >> 1)) * 4, perm_im = perm_re + 8 * 4;
+    const int perm_a = odd_b ? perm_im : perm_re, perm_b = odd_b ? perm_re : perm_im;
+
     // load order -> consumer order
     auto to_consumer = [&](const uint4 &raw) {
         uint4 v;
-        v.x = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.x);
-        v.y = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.y);
-        v.z = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.z);
-        v.w = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.w);
+        if constexpr (HALF) {
+            const int r1 = __builtin_amdgcn_ds_bpermute(perm_a, (int)(ld_im ? raw.z : raw.x));
+            const int r2 = __builtin_amdgcn_ds_bpermute(perm_b, (int)(ld_im ? raw.x : raw.z));
+            const int r3 = __builtin_amdgcn_ds_bpermute(perm_a, (int)(ld_im ? raw.w : raw.y));
+            const int r4 = __builtin_amdgcn_ds_bpermute(perm_b, (int)(ld_im ? raw.y : raw.w));
+            v.x = (uint32_t)(odd_b ? r2 : r1);   // re of bands 4b, 4b+1
+            v.y = (uint32_t)(odd_b ? r4 : r3);   // re of bands 4b+2, 4b+3
+            v.z = (uint32_t)(odd_b ? r1 : r2);   // im of bands 4b, 4b+1
+            v.w = (uint32_t)(odd_b ? r3 : r4);   // im of bands 4b+2, 4b+3
+        } else {
+            v.x = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.x);
+            v.y = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.y);
+            v.z = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.z);
+            v.w = (uint32_t)__builtin_amdgcn_ds_bpermute(perm_k, (int)raw.w);
+        }
         return v;
     };
 
@@ -267,7 +296,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
         const float4 e0 = *reinterpret_cast<const float4 *>(ph0 + r * 16);
         const float4 e1 = *reinterpret_cast<const float4 *>(ph0 + kPhasorHalfStride + r * 16);
         const float cs[4] = {e0.x, e0.z, e1.x, e1.z}, sn[4] = {e0.y, e0.w, e1.y, e1.w};
-        score_step<NG>(kd, cs, sn, tb, out);
+        score_step<NG, true, HALF>(kd, cs, sn, tb, out);
     };
 
     // one step for any four positions: move the base if that brings them into the table, else
@@ -290,7 +319,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
                     sn[k] = __builtin_amdgcn_sinf(x);
                     cs[k] = __builtin_amdgcn_cosf(x);
                 }
-                score_step<NG>(kd, cs, sn, tb, out);
+                score_step<NG, true, HALF>(kd, cs, sn, tb, out);
                 return;
             }
         }
@@ -314,7 +343,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 float out[NG];
-                score_step<NG, false>(kd[t], one, zero, tb, out);
+                score_step<NG, false, HALF>(kd[t], one, zero, tb, out);
 #pragma unroll
                 for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
             }
@@ -418,11 +447,15 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 }
 
 template <int G>
-tri_status launch_fast_g(const ScoreArgs &sa, int n_layers, hipStream_t st)
+tri_status launch_fast_g(const ScoreArgs &sa, int n_layers, bool half_split, hipStream_t st)
 {
     const bool paged = sa.c.block_shift >= 0;
-    auto kern = sa.c.k_rotated ? (paged ? score_mfma_kernel<G, true, true> : score_mfma_kernel<G, false, true>)
-                               : (paged ? score_mfma_kernel<G, true, false> : score_mfma_kernel<G, false, false>);
+    auto pick = [&](auto half) {
+        constexpr bool H = decltype(half)::value;
+        return sa.c.k_rotated ? (paged ? score_mfma_kernel<G, true, true, H> : score_mfma_kernel<G, false, true, H>)
+                              : (paged ? score_mfma_kernel<G, true, false, H> : score_mfma_kernel<G, false, false, H>);
+    };
+    auto kern = half_split ? pick(std::true_type{}) : pick(std::false_type{});
     const int lds = sa.c.k_rotated ? 0 : kPhasorBytes;   // no phasor table for post-RoPE keys
     if (lds && hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return hip_status("hipFuncSetAttribute(score_mfma_kernel)");
@@ -440,13 +473,13 @@ tri_status launch_phasor_table(double theta, uint4 *phasors, hipStream_t st)
     return hip_status("phasor_table_kernel");
 }
 
-tri_status launch_score_fast(int G, const ScoreArgs &sa, int n_layers, hipStream_t st)
+tri_status launch_score_fast(int G, const ScoreArgs &sa, int n_layers, bool half_split, hipStream_t st)
 {
     switch (G) {
-        case 1: return launch_fast_g<1>(sa, n_layers, st);
-        case 2: return launch_fast_g<2>(sa, n_layers, st);
-        case 4: return launch_fast_g<4>(sa, n_layers, st);
-        case 8: return launch_fast_g<8>(sa, n_layers, st);
+        case 1: return launch_fast_g<1>(sa, n_layers, half_split, st);
+        case 2: return launch_fast_g<2>(sa, n_layers, half_split, st);
+        case 4: return launch_fast_g<4>(sa, n_layers, half_split, st);
+        case 8: return launch_fast_g<8>(sa, n_layers, half_split, st);
     }
     set_error("group size %d not built (1, 2, 4, 8)", G);
     return TRI_ERR_UNSUPPORTED;

@@ -131,10 +131,12 @@ def test_wild_positions(oracle):
     run_and_check(oracle, cfg, mutate=mutate)
 
 
-def test_half_split_pairs(oracle):
-    """Band f = (x[f], x[f + d/2]): the same workload with every head vector permuted to that layout."""
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_half_split_pairs(oracle, dtype):
+    """Band f = (x[f], x[f + d/2]): the same workload with every head vector permuted to that layout
+    (bf16: MFMA kernel; fp32: generic kernel)."""
     cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=1, n_q_heads=8, n_kv_heads=2, seq_len=500,
-                        budget=64, n_calib=128)
+                        budget=64, n_calib=128, dtype=dtype)
 
     def mutate(w):
         for name in ("k", "q_samples"):
@@ -168,3 +170,18 @@ def test_post_rope_cache(oracle, dtype, pairs, paged):
         w["k"] = recipe.to_post_rope(w["k"], w["pos"], cfg.rope_theta, pairs, cfg.dtype)
 
     run_and_check(oracle, cfg, paged=paged, pairs=pairs, mutate=mutate, rotated=True)
+
+
+@pytest.mark.parametrize("pairs", [0, 1])
+def test_paged_blocks_of_eight(oracle, pairs):
+    """Blocks shorter than a 16-key group: the generic kernel scores bf16 keys (both pair layouts)."""
+    cfg = recipe.scaled(recipe.CONFIGS["c4_paged"], n_layers=1, n_seqs=2, n_q_heads=8, n_kv_heads=2, seq_len=600,
+                        min_seq_len=150, budget=100, n_calib=128, block_size=8)
+
+    def mutate(w):
+        if pairs:
+            for name in ("k", "q_samples"):
+                x = w[name]
+                w[name] = np.ascontiguousarray(np.concatenate([x[..., 0::2], x[..., 1::2]], axis=-1))
+
+    run_and_check(oracle, cfg, paged=True, inplace=True, pairs=pairs, mutate=mutate)
