@@ -145,7 +145,10 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps loop control scalar
     const int b = lane >> 2, i = lane & 3;
-    const int chunk = blockIdx.x;
+    // Workgroups go to the 8 XCDs round-robin by linear index, so with gridDim.x a multiple of 8 chunk c of
+    // every head-instance would land on XCD c -- and with ragged sequence lengths the XCDs that own the high
+    // chunks would idle.  Rotating the chunk index by the instance index spreads every chunk over all XCDs.
+    const int chunk = (blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x;
     const int s = blockIdx.y / c.n_kv_heads, h = blockIdx.y % c.n_kv_heads;
     const int l = blockIdx.z;
     const int N = c.seq_len[s];
@@ -206,10 +209,20 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     const int perm_k = (16 * i + b) * 4;   // ds_bpermute address: source lane of this lane's K piece
     const int perm_p = i * 4;              // source lane (4t + i) of this lane's position at step t, plus 16*t
 
+    // Paged: the wave's share (at most 1024 keys) spans at most 64 blocks plus one; their ids are read once,
+    // one per lane, so that no group's addresses wait on a block-table load behind the K loads in flight.
+    const int blk0 = PAGED ? (w0 >> c.block_shift) : 0;
+    int blk_ids = 0, blk_ids_hi = 0;
+    if constexpr (PAGED) {
+        blk_ids = bt[min(blk0 + lane, c.max_blocks - 1)];
+        blk_ids_hi = bt[min(blk0 + 64, c.max_blocks - 1)];
+    }
+
     // group starting at key n (a multiple of 16): uniform base pointers of its K rows and positions
     auto group_ptrs = [&](int n, const char *&kp, const int32_t *&pq) {
         if constexpr (PAGED) {
-            const int blk = __builtin_amdgcn_readfirstlane(bt[n >> c.block_shift]);
+            const int rel = (n >> c.block_shift) - blk0;
+            const int blk = rel < 64 ? __builtin_amdgcn_readlane(blk_ids, rel) : __builtin_amdgcn_readfirstlane(blk_ids_hi);
             const int slot = n & bmask;
             kp = krow + (int64_t)blk * c.stride_sb * 2 + (int64_t)slot * slot_bytes;
             pq = prow + (int64_t)blk * c.pos_stride_sb + slot;

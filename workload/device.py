@@ -41,7 +41,7 @@ def lib():
         L.wl_fill_normal.restype = i32
         L.wl_fill_normal.argtypes = [vp, i32, i64, u64, u64, vp]
         L.wl_stream_probe.restype = i64
-        L.wl_stream_probe.argtypes = [vp, i64, vp, i32, vp]
+        L.wl_stream_probe.argtypes = [vp, i64, vp, i32, i32, vp]
         _lib = L
     return _lib
 
@@ -134,20 +134,22 @@ def generate(cfg, positions=None, layers=None):
 
 def hbm_probe(gib=16, reps=5):
     """Streaming-read rate of this GPU, alone and with a thin write stream mixed in (1 write byte per 16 / 64 /
-    256 read bytes).  Returns {label: GB/s of reads}."""
+    256 read bytes), with plain loads and with loads that carry the non-temporal hint.  Returns {label: GB/s of
+    reads}."""
     n = gib << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
     dst = torch.empty(n // 16 + 64, dtype=torch.uint8, device="cuda")
     out = {}
-    for label, every in (("read_only", 0), ("read_with_1/16_writes", 1), ("read_with_1/64_writes", 4),
-                         ("read_with_1/256_writes", 16)):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        got = lib().wl_stream_probe(src.data_ptr(), n, dst.data_ptr(), every, _stream())
-        assert got > 0
-        e0.record()
-        for _ in range(reps):
-            lib().wl_stream_probe(src.data_ptr(), n, dst.data_ptr(), every, _stream())
-        e1.record()
-        torch.cuda.synchronize()
-        out[label] = round(got * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    for nt in (0, 1):
+        for label, every in (("read_only", 0), ("read_with_1/16_writes", 1), ("read_with_1/64_writes", 4),
+                             ("read_with_1/256_writes", 16)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            got = lib().wl_stream_probe(src.data_ptr(), n, dst.data_ptr(), every, nt, _stream())
+            assert got > 0
+            e0.record()
+            for _ in range(reps):
+                lib().wl_stream_probe(src.data_ptr(), n, dst.data_ptr(), every, nt, _stream())
+            e1.record()
+            torch.cuda.synchronize()
+            out[label + ("/nt_loads" if nt else "")] = round(got * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
     return out

@@ -117,6 +117,9 @@ __global__ __launch_bounds__(256) void normal_kernel(NormalArgs a)
 // Streaming probe: every wave reads its own contiguous range 4 KB at a time (16 bytes per lane and load) and,
 // every `write_every` reads (0 = never), writes 256 bytes.  Measures what the HBM delivers for a pure read
 // stream and for a read stream with a thin write stream mixed in -- the two regimes of the score kernel.
+typedef unsigned int probe_u4 __attribute__((ext_vector_type(4)));
+
+template <bool NT>   // NT: loads carry the non-temporal hint (data read once)
 __global__ __launch_bounds__(512) void stream_probe_kernel(const uint4 *__restrict__ in, uint32_t *__restrict__ out,
                                                            uint32_t *sink, int64_t per_wave16, int write_every)
 {
@@ -129,7 +132,14 @@ __global__ __launch_bounds__(512) void stream_probe_kernel(const uint4 *__restri
     for (int64_t i = 0; i + 256 <= per_wave16; i += 256, ++it) {
         uint4 a[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) a[u] = p[i + u * 64 + lane];
+        for (int u = 0; u < 4; ++u) {
+            if constexpr (NT) {
+                const probe_u4 t = __builtin_nontemporal_load(reinterpret_cast<const probe_u4 *>(p + i + u * 64 + lane));
+                a[u] = make_uint4(t.x, t.y, t.z, t.w);
+            } else {
+                a[u] = p[i + u * 64 + lane];
+            }
+        }
 #pragma unroll
         for (int u = 0; u < 4; ++u) acc ^= a[u].x ^ a[u].y ^ a[u].z ^ a[u].w;
         if (write_every > 0 && (it % write_every) == write_every - 1) {
@@ -146,15 +156,19 @@ extern "C" {
 
 // Launch the streaming probe over `bytes` of `in` (device); `out` needs bytes/16 + 4 bytes.  Returns the number
 // of bytes the launch reads, or a negative value on error.
-int64_t wl_stream_probe(const void *in, int64_t bytes, void *out, int write_every, void *stream)
+int64_t wl_stream_probe(const void *in, int64_t bytes, void *out, int write_every, int nontemporal, void *stream)
 {
     if (!in || !out || bytes < (1 << 24)) return -1;
     const int wgs = 4096;
     const int64_t waves = (int64_t)wgs * 8;
     const int64_t per = (bytes / 16 / waves) / 256 * 256;
     uint32_t *o = reinterpret_cast<uint32_t *>(out);
-    hipLaunchKernelGGL(stream_probe_kernel, dim3(wgs), dim3(512), 0, (hipStream_t)stream,
-                       reinterpret_cast<const uint4 *>(in), o, o + bytes / 64, per, write_every);
+    if (nontemporal)
+        hipLaunchKernelGGL(stream_probe_kernel<true>, dim3(wgs), dim3(512), 0, (hipStream_t)stream,
+                           reinterpret_cast<const uint4 *>(in), o, o + bytes / 64, per, write_every);
+    else
+        hipLaunchKernelGGL(stream_probe_kernel<false>, dim3(wgs), dim3(512), 0, (hipStream_t)stream,
+                           reinterpret_cast<const uint4 *>(in), o, o + bytes / 64, per, write_every);
     return hipGetLastError() == hipSuccess ? per * waves * 16 : -4;
 }
 
