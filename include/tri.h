@@ -119,6 +119,33 @@ const char *tri_last_error(void);
 tri_status tri_build_centers(const tri_model *model, const void *q_samples, int32_t q_dtype,
                              int64_t n_tokens, float *centers_out, void *stream);
 
+/*
+ * The same calibration as a stream of chunks (Appendix H calibrates on 50 k to 960 k tokens, more than fits
+ * beside a model): every call adds the sums of its chunk -- sum Re q_f, sum Im q_f, sum ||q_f|| -- to
+ *   sums  device [n_layers][n_q_heads][head_dim/2][3] double
+ * (first != 0: the chunk's sums overwrite `sums` instead, so no separate clearing is needed), and
+ * tri_centers_finalize divides by the total number of tokens and writes the table tri_build_centers writes.
+ * Chunks are accumulated in the order of the calls on the stream; within a chunk the order is fixed.
+ */
+tri_status tri_centers_accumulate(const tri_model *model, const void *q_samples, int32_t q_dtype,
+                                  int64_t n_tokens, double *sums, int32_t first, void *stream);
+tri_status tri_centers_finalize(const tri_model *model, const double *sums, int64_t total_tokens,
+                                float *centers_out, void *stream);
+
+/*
+ * Concentration and dominant-band diagnostics of a statistics table (Appendix B.5, B.7):
+ *   mrl_out        device [n_layers][n_q_heads][F] float: R_f = ||E[q_f]|| / E||q_f|| (0 for an all-zero band)
+ *   contrib_out    NULL, or device [n_layers][n_q_heads][F] float: C_f = E||q_f|| * E||k_f||, the KV head of
+ *                  query head h being h / G
+ *   top_bands_out  NULL, or device [n_layers][n_q_heads][top_k] int32: the top_k bands by C_f, largest first,
+ *                  equal contributions by ascending band
+ *   k_centers      device [n_layers][n_kv_heads][F][3]: the table tri_build_centers writes for key samples
+ *                  (built with a model whose n_q_heads is n_kv_heads); may be NULL when only mrl_out is wanted
+ */
+tri_status tri_band_diagnostics(const tri_model *model, const float *q_centers, const float *k_centers,
+                                float *mrl_out, float *contrib_out, int32_t top_k,
+                                int32_t *top_bands_out, void *stream);
+
 /* Bytes of scratch tri_score / tri_select_topk / tri_compress_step need for this model, cache
  * geometry and budget (the maximum over the three).  0 on invalid arguments. */
 size_t tri_workspace_size(const tri_model *model, const tri_cache *cache, int32_t budget);

@@ -102,6 +102,55 @@ int tri_oracle_centers(const void *q, int dtype, int64_t T, int L, int Hq, int d
 }
 
 /*
+ * Appendix B.5, Mean Resultant Length per frequency band:
+ *   R_f = ||E[q_f]|| / E||q_f||
+ * (a band whose samples are all zero has R_f = 0 by convention).
+ *   stats [n][F][3] as written by tri_oracle_centers, out [n][F] double
+ */
+int tri_oracle_mrl(const float *stats, int64_t n, int F, double *out)
+{
+    for (int64_t i = 0; i < n * F; ++i) {
+        double re = (double)stats[3 * i + 0], im = (double)stats[3 * i + 1], ab = (double)stats[3 * i + 2];
+        out[i] = ab > 0.0 ? hypot(re, im) / ab : 0.0;
+    }
+    return 0;
+}
+
+/*
+ * Appendix B.7, expected contribution of band f to the attention logit and the dominant bands:
+ *   C_f = E||q_f|| * E||k_f||,   bands ranked by C_f, the top K kept
+ * (equal contributions: the lower band first).  Query head h of the L x Hq heads is paired with KV
+ * head h / G of the same layer.
+ *   qstats [L][Hq][F][3], kstats [L][Hkv][F][3], contrib [L][Hq][F] double, top [L][Hq][K] int32
+ */
+int tri_oracle_band_contrib(const float *qstats, const float *kstats, int L, int Hq, int Hkv, int F, int K,
+                            double *contrib, int32_t *top)
+{
+    if (Hkv <= 0 || Hq % Hkv || K < 0 || K > F) return -1;
+    int G = Hq / Hkv;
+    for (int l = 0; l < L; ++l)
+        for (int h = 0; h < Hq; ++h) {
+            const float *q = qstats + ((int64_t)l * Hq + h) * F * 3;
+            const float *k = kstats + ((int64_t)l * Hkv + h / G) * F * 3;
+            double *c = contrib + ((int64_t)l * Hq + h) * F;
+            for (int f = 0; f < F; ++f) c[f] = (double)q[3 * f + 2] * (double)k[3 * f + 2];
+            /* selection sort of the K largest: plain and obviously stable */
+            int32_t *t = top + ((int64_t)l * Hq + h) * K;
+            for (int r = 0; r < K; ++r) {
+                int best = -1;
+                for (int f = 0; f < F; ++f) {
+                    int taken = 0;
+                    for (int p = 0; p < r; ++p) taken |= t[p] == f;
+                    if (taken) continue;
+                    if (best < 0 || c[f] > c[best]) best = f;
+                }
+                t[r] = best;
+            }
+        }
+    return 0;
+}
+
+/*
  * Section 4.1, trigonometric series score:
  *   S_trig(k, x) = sum_f ||E[q_f]|| * ||k_f|| * cos(omega_f * x + phi_f),
  *   phi_f = arg E[q_f] - arg k_f,

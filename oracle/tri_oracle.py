@@ -44,6 +44,10 @@ def lib():
         L.tri_oracle_omega.argtypes = [dbl, i32, i32]
         L.tri_oracle_centers.restype = i32
         L.tri_oracle_centers.argtypes = [vp, i32, i64, i32, i32, i32, i32, vp]
+        L.tri_oracle_mrl.restype = i32
+        L.tri_oracle_mrl.argtypes = [vp, i64, i32, vp]
+        L.tri_oracle_band_contrib.restype = i32
+        L.tri_oracle_band_contrib.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp]
         L.tri_oracle_s_trig.restype = dbl
         L.tri_oracle_s_trig.argtypes = [vp, vp, i32, i64, i32, i32, dbl, i64]
         for name in ("tri_oracle_s_norm", "tri_oracle_s_norm_mrl", "tri_oracle_s_norm0"):
@@ -103,6 +107,27 @@ def centers(q, pairs=PAIR_INTERLEAVED):
     rc = lib().tri_oracle_centers(_ptr(q), _dtype_code(q), T, L, Hq, d, pairs, _ptr(out))
     assert rc == 0
     return out
+
+
+def mrl(stats):
+    """stats [..., F, 3] -> R_f [..., F] float64 (Appendix B.5)."""
+    stats = _c(stats, np.float32)
+    F = stats.shape[-2]
+    out = np.empty(stats.shape[:-1], dtype=np.float64)
+    rc = lib().tri_oracle_mrl(_ptr(stats), stats.size // (3 * F), F, _ptr(out))
+    assert rc == 0
+    return out
+
+
+def band_contrib(qstats, kstats, top_k):
+    """qstats [L][Hq][F][3], kstats [L][Hkv][F][3] -> (C_f [L][Hq][F] float64, dominant bands [L][Hq][top_k] int32)."""
+    qstats, kstats = _c(qstats, np.float32), _c(kstats, np.float32)
+    L, Hq, F, _ = qstats.shape
+    contrib = np.empty((L, Hq, F), dtype=np.float64)
+    top = np.empty((L, Hq, top_k), dtype=np.int32)
+    rc = lib().tri_oracle_band_contrib(_ptr(qstats), _ptr(kstats), L, Hq, kstats.shape[1], F, top_k, _ptr(contrib), _ptr(top))
+    assert rc == 0
+    return contrib, top
 
 
 def s_trig(stats, key, theta, dist, pairs=PAIR_INTERLEAVED):

@@ -17,7 +17,7 @@ TRI_F32, TRI_BF16 = 0, 1
 TRI_PAIR_INTERLEAVED, TRI_PAIR_HALF = 0, 1
 TRI_SCORE_FULL, TRI_SCORE_TRIG_ONLY, TRI_SCORE_NORM_ONLY, TRI_SCORE_NORM_UNWEIGHTED = 0, 1, 2, 3
 
-EXPORTS = ["tri_last_error", "tri_build_centers", "tri_workspace_size", "tri_score", "tri_select_topk",
+EXPORTS = ["tri_last_error", "tri_build_centers", "tri_centers_accumulate", "tri_centers_finalize", "tri_band_diagnostics", "tri_workspace_size", "tri_score", "tri_select_topk",
            "tri_compact", "tri_compact_fill", "tri_compress_step", "tri_timing_attach", "tri_timing_detach"]
 
 
@@ -60,6 +60,12 @@ def lib():
         L.tri_last_error.argtypes = []
         L.tri_build_centers.restype = i32
         L.tri_build_centers.argtypes = [ctypes.POINTER(TriModel), vp, i32, i64, vp, vp]
+        L.tri_centers_accumulate.restype = i32
+        L.tri_centers_accumulate.argtypes = [ctypes.POINTER(TriModel), vp, i32, i64, vp, i32, vp]
+        L.tri_centers_finalize.restype = i32
+        L.tri_centers_finalize.argtypes = [ctypes.POINTER(TriModel), vp, i64, vp, vp]
+        L.tri_band_diagnostics.restype = i32
+        L.tri_band_diagnostics.argtypes = [ctypes.POINTER(TriModel), vp, vp, vp, vp, i32, vp, vp]
         L.tri_workspace_size.restype = ctypes.c_size_t
         L.tri_workspace_size.argtypes = [ctypes.POINTER(TriModel), ctypes.POINTER(TriCache), i32]
         L.tri_score.restype = i32
@@ -152,6 +158,23 @@ def tri_build_centers(model, q_samples, centers_out, stream=None):
     assert q_samples.is_contiguous() and centers_out.is_contiguous() and centers_out.dtype == torch.float32
     _check(lib().tri_build_centers(model.ref, _p(q_samples), _dtype(q_samples), q_samples.shape[0], _p(centers_out),
                                    _stream(stream)))
+
+
+def tri_centers_accumulate(model, q_samples, sums, first, stream=None):
+    """Adds the sums of one chunk q_samples [T][L][Hq][d] to sums [L][Hq][F][3] float64 (first: overwrite)."""
+    assert q_samples.is_contiguous() and sums.is_contiguous() and sums.dtype == torch.float64
+    _check(lib().tri_centers_accumulate(model.ref, _p(q_samples), _dtype(q_samples), q_samples.shape[0], _p(sums),
+                                        int(bool(first)), _stream(stream)))
+
+
+def tri_centers_finalize(model, sums, total_tokens, centers_out, stream=None):
+    assert sums.is_contiguous() and sums.dtype == torch.float64 and centers_out.dtype == torch.float32
+    _check(lib().tri_centers_finalize(model.ref, _p(sums), int(total_tokens), _p(centers_out), _stream(stream)))
+
+
+def tri_band_diagnostics(model, q_centers, k_centers, mrl_out, contrib_out=None, top_k=0, top_bands_out=None, stream=None):
+    _check(lib().tri_band_diagnostics(model.ref, _p(q_centers), _p(k_centers), _p(mrl_out), _p(contrib_out), int(top_k),
+                                      _p(top_bands_out), _stream(stream)))
 
 
 def tri_workspace_size(model, cache, budget):

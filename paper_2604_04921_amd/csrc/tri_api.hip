@@ -224,7 +224,53 @@ tri_status tri_build_centers(const tri_model *model, const void *q_samples, int3
         set_error("tri_build_centers: q_samples, centers_out, n_tokens >= 1 and a known dtype required");
         return TRI_ERR_INVALID_ARG;
     }
-    return launch_centers(*model, q_samples, q_dtype, n_tokens, centers_out, (hipStream_t)stream);
+    return launch_centers(*model, q_samples, q_dtype, n_tokens, centers_out, nullptr, 0, (hipStream_t)stream);
+}
+
+tri_status tri_centers_accumulate(const tri_model *model, const void *q_samples, int32_t q_dtype, int64_t n_tokens,
+                                  double *sums, int32_t first, void *stream)
+{
+    tri_status rc = check_model(model);
+    if (rc != TRI_OK) return rc;
+    if (!q_samples || !sums || n_tokens < 1 || (q_dtype != TRI_F32 && q_dtype != TRI_BF16)) {
+        set_error("tri_centers_accumulate: q_samples, sums, n_tokens >= 1 and a known dtype required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    return launch_centers(*model, q_samples, q_dtype, n_tokens, nullptr, sums, first ? 1 : 0, (hipStream_t)stream);
+}
+
+tri_status tri_centers_finalize(const tri_model *model, const double *sums, int64_t total_tokens, float *centers_out,
+                                void *stream)
+{
+    tri_status rc = check_model(model);
+    if (rc != TRI_OK) return rc;
+    if (!sums || !centers_out || total_tokens < 1) {
+        set_error("tri_centers_finalize: sums, centers_out and total_tokens >= 1 required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    return launch_centers_finalize(*model, sums, total_tokens, centers_out, (hipStream_t)stream);
+}
+
+tri_status tri_band_diagnostics(const tri_model *model, const float *q_centers, const float *k_centers,
+                                float *mrl_out, float *contrib_out, int32_t top_k, int32_t *top_bands_out,
+                                void *stream)
+{
+    tri_status rc = check_model(model);
+    if (rc != TRI_OK) return rc;
+    if (!q_centers || !mrl_out) {
+        set_error("tri_band_diagnostics: q_centers and mrl_out required");
+        return TRI_ERR_INVALID_ARG;
+    }
+    if ((contrib_out || top_bands_out) && !k_centers) {
+        set_error("tri_band_diagnostics: the band contributions need k_centers");
+        return TRI_ERR_INVALID_ARG;
+    }
+    if (top_bands_out && (top_k < 1 || top_k > kBands)) {
+        set_error("tri_band_diagnostics: top_k must be in [1, %d]", kBands);
+        return TRI_ERR_INVALID_ARG;
+    }
+    return launch_diagnostics(*model, q_centers, k_centers, mrl_out, contrib_out, top_k, top_bands_out,
+                              (hipStream_t)stream);
 }
 
 size_t tri_workspace_size(const tri_model *model, const tri_cache *cache, int32_t budget)

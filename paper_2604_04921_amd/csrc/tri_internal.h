@@ -73,7 +73,11 @@ bool timing_next(hipEvent_t *start, hipEvent_t *stop);
 
 // launchers (each validates nothing; the entry points in tri_api.hip do)
 tri_status launch_centers(const tri_model &m, const void *q, int32_t q_dtype, int64_t n_tokens,
-                          float *out, hipStream_t st);
+                          float *out, double *sums, int32_t first, hipStream_t st);
+tri_status launch_centers_finalize(const tri_model &m, const double *sums, int64_t total_tokens, float *out,
+                                   hipStream_t st);
+tri_status launch_diagnostics(const tri_model &m, const float *q_centers, const float *k_centers, float *mrl,
+                              float *contrib, int32_t top_k, int32_t *top, hipStream_t st);
 tri_status launch_score(const tri_model &m, const float *centers, const tri_cache &c, float *final_out,
                         float *raw_out, char *ws, const Workspace &wl, hipStream_t st);
 // final_scores given: select on them; else form them from raw + stats (scratch: keys of long sequences)

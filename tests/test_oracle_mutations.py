@@ -30,6 +30,9 @@ MUTATIONS = [
     ("w/o R keeps the weighted term", "if (variant == 0 || variant == 2) S += tri_oracle_s_norm(", "if (variant != 1) S += tri_oracle_s_norm("),
     ("trig-only keeps the norm term", "if (variant == 3) S += tri_oracle_s_norm0(", "if (variant == 3 || variant == 1) S += tri_oracle_s_norm0("),
     ("unweighted norm uses the centre modulus", "s += qabs * hypot(kre, kim);", "s += hypot((double)stats[3 * f], (double)stats[3 * f + 1]) * hypot(kre, kim);"),
+    ("MRL inverted", "out[i] = ab > 0.0 ? hypot(re, im) / ab : 0.0;", "out[i] = ab > 0.0 ? ab / hypot(re, im) : 0.0;"),
+    ("band contribution from the centre modulus", "c[f] = (double)q[3 * f + 2] * (double)k[3 * f + 2];", "c[f] = hypot((double)q[3 * f], (double)q[3 * f + 1]) * (double)k[3 * f + 2];"),
+    ("dominant bands: KV head of the wrong group", "kstats + ((int64_t)l * Hkv + h / G) * F * 3;", "kstats + ((int64_t)l * Hkv + h % Hkv) * F * 3;"),
     ("compaction source off by one", "(int64_t)idx[j] * src_stride_bytes", "(int64_t)(idx[j] + 1) * src_stride_bytes"),
 ]
 

@@ -471,3 +471,54 @@ def test_post_rope_cache(oracle, pairs):
             stored = np.stack([stored[: d // 2], stored[d // 2:]], axis=-1).reshape(-1)
         brute = float(np.dot(rope_rotate(centre, 3100, theta), stored))
         assert t[0, n] == pytest.approx(brute, rel=1e-9, abs=1e-9)
+
+
+# ---- concentration and dominant-band diagnostics (Appendix B.5, B.7) -----------------------------
+
+def test_mrl_of_unit_vectors_and_limits(oracle):
+    """P19: for unit vectors R is the length of their mean (first equation of Appendix B.5): n equally spaced
+    directions give 0, one repeated direction gives 1, two directions at angle a give cos(a/2); scaling every
+    sample by a common factor changes nothing."""
+    n, F = 12, 4
+    q = np.zeros((n, 1, 1, 2 * F), dtype=np.float32)
+    ang = 2 * np.pi * np.arange(n) / n
+    q[:, 0, 0, 0], q[:, 0, 0, 1] = np.cos(ang), np.sin(ang)                  # band 0: uniform on the circle
+    q[:, 0, 0, 2], q[:, 0, 0, 3] = np.cos(0.7), np.sin(0.7)                  # band 1: one direction
+    a = 1.1
+    half = np.where(np.arange(n) % 2 == 0, 0.0, a)
+    q[:, 0, 0, 4], q[:, 0, 0, 5] = np.cos(half), np.sin(half)                # band 2: two directions
+    rng = np.random.default_rng(5)
+    u = rng.uniform(0, 2 * np.pi, n)
+    q[:, 0, 0, 6], q[:, 0, 0, 7] = np.cos(u), np.sin(u)                      # band 3: random unit vectors
+    R = oracle.mrl(oracle.centers(q))[0, 0]
+    assert R[0] == pytest.approx(0.0, abs=1e-6)
+    assert R[1] == pytest.approx(1.0, abs=1e-6)
+    assert R[2] == pytest.approx(math.cos(a / 2), abs=1e-6)
+    assert R[3] == pytest.approx(abs(np.mean(np.exp(1j * u))), abs=1e-6)
+    R5 = oracle.mrl(oracle.centers(q * np.float32(5.0)))[0, 0]
+    np.testing.assert_allclose(R5, R, atol=1e-6)
+    assert np.all(R <= 1.0 + 1e-6) and np.all(R >= 0.0)
+    assert oracle.mrl(np.zeros((1, 3), dtype=np.float32))[0] == 0.0
+
+
+def test_band_contribution_and_dominant_bands(oracle):
+    """P20: C_f = E|q_f| E|k_f| (Appendix B.7) against numpy means of moduli; the dominant bands are a stable
+    descending argsort; query head h pairs with KV head h // G."""
+    rng = np.random.default_rng(6)
+    T, L, Hq, Hkv, d = 50, 2, 4, 2, 16
+    q = rng.standard_normal((T, L, Hq, d)).astype(np.float32) * rng.uniform(0.2, 3.0, size=(1, L, Hq, d)).astype(np.float32)
+    k = rng.standard_normal((T, L, Hkv, d)).astype(np.float32) * rng.uniform(0.2, 3.0, size=(1, L, Hkv, d)).astype(np.float32)
+    qs, ks = oracle.centers(q), oracle.centers(k)
+    C, top = oracle.band_contrib(qs, ks, 3)
+    qm = np.abs(q[..., 0::2].astype(np.float64) + 1j * q[..., 1::2]).mean(axis=0)
+    km = np.abs(k[..., 0::2].astype(np.float64) + 1j * k[..., 1::2]).mean(axis=0)
+    for l in range(L):
+        for h in range(Hq):
+            ref = qm[l, h] * km[l, h // (Hq // Hkv)]
+            np.testing.assert_allclose(C[l, h], ref, rtol=1e-6)
+            order = np.argsort(-C[l, h], kind="stable")[:3]
+            np.testing.assert_array_equal(top[l, h], order)
+    # ties: equal contributions keep the lower band first
+    flat = np.ones((1, 1, 8, 3), dtype=np.float32)
+    _, t = oracle.band_contrib(flat, flat, 4)
+    np.testing.assert_array_equal(t[0, 0], [0, 1, 2, 3])
