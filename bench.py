@@ -147,7 +147,8 @@ def main():
     if args.fill and step_bytes:   # only the kept keys stored beyond the new length move
         moved = int((kept_idx >= kept_cnt[..., None]).sum())
         step_bytes = 260 * keys + 1032 * moved
-    roofline = {"bound": "hbm", "kernel": "score_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+    mfma_path = eb == 2 and (cfg.block_size == 0 or cfg.block_size >= 16)   # which of the two score kernels ran
+    roofline = {"bound": "hbm", "kernel": "score_mfma_kernel" if mfma_path else "score_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get("%s/%s" % (cfg.name, mode)),
                 "launch_ms": round(launch_ms, 4), "launches_per_step": launches,

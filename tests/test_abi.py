@@ -45,3 +45,14 @@ def test_host_validation_rejects_bad_arguments():
     assert L.tri_score(ctypes.byref(m), None, ctypes.byref(c), None, None, None, 0, None) == T.TRI_ERR_INVALID_ARG
     assert L.tri_timing_attach(None, 4) == T.TRI_ERR_INVALID_ARG
     assert L.tri_timing_detach() == 0
+    # entry points added around the four primitives
+    m = T.TriModel(1, 4, 1, 128, 1e6, 0, 3, offs.ctypes.data_as(ctypes.c_void_p), 7)   # unknown score variant
+    assert L.tri_build_centers(ctypes.byref(m), None, 0, 1, None, None) == T.TRI_ERR_INVALID_ARG
+    assert b"variant" in L.tri_last_error()
+    m = T.TriModel(1, 4, 1, 128, 1e6, 0, 3, offs.ctypes.data_as(ctypes.c_void_p), 0)
+    assert L.tri_centers_accumulate(ctypes.byref(m), None, 0, 1, None, 1, None) == T.TRI_ERR_INVALID_ARG
+    assert L.tri_centers_finalize(ctypes.byref(m), None, 0, None, None) == T.TRI_ERR_INVALID_ARG
+    assert L.tri_band_diagnostics(ctypes.byref(m), None, None, None, None, 0, None, None) == T.TRI_ERR_INVALID_ARG
+    assert L.tri_compact_fill(ctypes.byref(m), ctypes.byref(c), 16, None, None, None, None) == T.TRI_ERR_INVALID_ARG
+    assert L.tri_compress_step(ctypes.byref(m), None, ctypes.byref(c), None, 16, None, None, None, None, 0, None) \
+        == T.TRI_ERR_INVALID_ARG
