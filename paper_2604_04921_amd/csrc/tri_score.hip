@@ -37,13 +37,15 @@ __device__ __forceinline__ void unit_phasor(double t, double rev, double *c, dou
     sincos(kTwoPi * x, s, c);
 }
 
-// grid (Hq, L), block F: thread = band
+constexpr int kFoldSeqs = 8;   // sequences per workgroup
+
+// grid (Hq, L, ceil(S / kFoldSeqs)), block F: thread = band
 __global__ __launch_bounds__(kBands) void fold_kernel(FoldArgs a)
 {
     const int f = threadIdx.x, qh = blockIdx.x, l = blockIdx.y;
     // Section 2.1: omega_f = theta^(-2f/d); kept as revolutions per position
     const double rev = pow(a.theta, -2.0 * (double)f / (double)kHeadDim) / kTwoPi;
-    if (qh == 0 && l == 0) a.band_rev[f] = rev;
+    if (qh == 0 && l == 0 && blockIdx.z == 0) a.band_rev[f] = rev;
     double er = 0.0, ei = 0.0;
     for (int j = 0; j < a.n_off; ++j) {
         double c, s;
@@ -61,7 +63,8 @@ __global__ __launch_bounds__(kBands) void fold_kernel(FoldArgs a)
     const double ar = trig_on ? qr * er - qi * ei : 0.0, ai = trig_on ? qr * ei + qi * er : 0.0;
     const double cn = !norm_on ? 0.0 : a.variant == TRI_SCORE_NORM_UNWEIGHTED ? qa : qa - hypot(qr, qi);
     const int h = qh / a.G, g = qh % a.G;
-    for (int s = 0; s < a.S; ++s) {
+    const int s_end = min(a.S, ((int)blockIdx.z + 1) * kFoldSeqs);
+    for (int s = blockIdx.z * kFoldSeqs; s < s_end; ++s) {
         double c, sn;
         unit_phasor((double)a.cur_pos[s], rev, &c, &sn);
         float *t = a.table + (((((int64_t)l * a.S + s) * a.Hkv + h) * kBands + f) * 3) * a.G;
@@ -383,7 +386,8 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     fo.n_off = m.n_offsets;
     fo.variant = m.score_variant;
     for (int j = 0; j < m.n_offsets; ++j) fo.offsets[j] = m.offsets[j];
-    hipLaunchKernelGGL(fold_kernel, dim3(m.n_q_heads, m.n_layers), dim3(kBands), 0, st, fo);
+    hipLaunchKernelGGL(fold_kernel, dim3(m.n_q_heads, m.n_layers, (c.n_seqs + kFoldSeqs - 1) / kFoldSeqs), dim3(kBands), 0,
+                       st, fo);
     tri_status rc = hip_status("fold_kernel");
     if (rc != TRI_OK) return rc;
 
