@@ -22,7 +22,7 @@
  *   - Return value: TRI_OK or a negative tri_status.  Nothing aborts or throws.
  *     tri_last_error() returns a static string describing the last failure on the calling thread.
  *   - Non-finite key or statistics values: behaviour undefined.
- *   - head_dim must be 128 (64 frequency bands); n_q_heads / n_kv_heads (= G) must be 1, 2, 4 or 8;
+ *   - head_dim must be 128 (64 frequency bands); n_q_heads / n_kv_heads (= G) must be between 1 and 8;
  *     positions, cur_pos and cur_pos + max(offsets) must be below 2^62 in magnitude (positions
  *     and cur_pos are int32).
  */

@@ -19,18 +19,34 @@ def hipcc():
 
 
 def build(verbose=False, extra=()):
-    """Compile every .hip source and link libtri.so.  Always recompiles."""
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-shared", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    # hipcc's host pass does not know the packed-fp32 feature name and says so: harmless
-    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+    """Compile every .hip source (in parallel, one hipcc process each) and link libtri.so.  Always recompiles."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+
+    def clean(text):   # hipcc's host pass does not know the packed-fp32 feature name and says so: harmless
+        return "\n".join(l for l in text.splitlines() if "packed-fp32-ops" not in l)
+
+    with tempfile.TemporaryDirectory(prefix="libtri_build_") as tmp:
+        def compile_one(src):
+            obj = os.path.join(tmp, src.replace(".hip", ".o"))
+            cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-c", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+                   os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+            return src, obj, res.returncode, clean(res.stdout)
+
+        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as ex:
+            results = list(ex.map(compile_one, SOURCES))
+        for src, _, rc, out in results:
+            if rc != 0:
+                raise RuntimeError("hipcc failed on %s:\n%s" % (src, out))
+            if verbose and out.strip():
+                print(out)
+        cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *[r[1] for r in results], "-o", LIB]
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("link failed:\n" + clean(res.stdout))
     return LIB
 
 

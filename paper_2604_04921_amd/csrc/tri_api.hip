@@ -51,8 +51,8 @@ tri_status check_model(const tri_model *m)
         return TRI_ERR_UNSUPPORTED;
     }
     const int G = m->n_q_heads / m->n_kv_heads;
-    if (G != 1 && G != 2 && G != 4 && G != 8) {
-        set_error("group size %d not built (1, 2, 4, 8)", G);
+    if (G < 1 || G > kMaxGroup) {
+        set_error("group size %d not built (1 to 8)", G);
         return TRI_ERR_UNSUPPORTED;
     }
     if (!(m->rope_theta > 1.0)) {

@@ -403,10 +403,14 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     switch (G) {
         case 1: return launch_score_g<1>(m, c, sa, fa, final_out, st);
         case 2: return launch_score_g<2>(m, c, sa, fa, final_out, st);
+        case 3: return launch_score_g<3>(m, c, sa, fa, final_out, st);
         case 4: return launch_score_g<4>(m, c, sa, fa, final_out, st);
+        case 5: return launch_score_g<5>(m, c, sa, fa, final_out, st);
+        case 6: return launch_score_g<6>(m, c, sa, fa, final_out, st);
+        case 7: return launch_score_g<7>(m, c, sa, fa, final_out, st);
         case 8: return launch_score_g<8>(m, c, sa, fa, final_out, st);
     }
-    set_error("group size %d not built (1, 2, 4, 8)", G);
+    set_error("group size %d not built (1 to 8)", G);
     return TRI_ERR_UNSUPPORTED;
 }
 

@@ -26,7 +26,7 @@ constexpr int kPhasorHalfStride = 16 * kPhasorBlockStride;      // bytes per hal
 constexpr int kPhasorBytes = 2 * kPhasorHalfStride;
 
 tri_status launch_phasor_table(double theta, uint4 *phasors, hipStream_t st);
-// bf16 keys; G in {1, 2, 4, 8}
+// bf16 keys; G in 1..8
 tri_status launch_score_fast(int G, const ScoreArgs &sa, int n_layers, bool half_split, hipStream_t st);
 
 }  // namespace tri

@@ -491,10 +491,14 @@ tri_status launch_score_fast(int G, const ScoreArgs &sa, int n_layers, bool half
     switch (G) {
         case 1: return launch_fast_g<1>(sa, n_layers, half_split, st);
         case 2: return launch_fast_g<2>(sa, n_layers, half_split, st);
+        case 3: return launch_fast_g<3>(sa, n_layers, half_split, st);
         case 4: return launch_fast_g<4>(sa, n_layers, half_split, st);
+        case 5: return launch_fast_g<5>(sa, n_layers, half_split, st);
+        case 6: return launch_fast_g<6>(sa, n_layers, half_split, st);
+        case 7: return launch_fast_g<7>(sa, n_layers, half_split, st);
         case 8: return launch_fast_g<8>(sa, n_layers, half_split, st);
     }
-    set_error("group size %d not built (1, 2, 4, 8)", G);
+    set_error("group size %d not built (1 to 8)", G);
     return TRI_ERR_UNSUPPORTED;
 }
 

@@ -451,10 +451,14 @@ tri_status launch_select(const tri_model &m, const float *final_scores, const fl
     switch (m.n_q_heads / m.n_kv_heads) {
         case 1: return launch_select_g<1>(sa, n_inst, st);
         case 2: return launch_select_g<2>(sa, n_inst, st);
+        case 3: return launch_select_g<3>(sa, n_inst, st);
         case 4: return launch_select_g<4>(sa, n_inst, st);
+        case 5: return launch_select_g<5>(sa, n_inst, st);
+        case 6: return launch_select_g<6>(sa, n_inst, st);
+        case 7: return launch_select_g<7>(sa, n_inst, st);
         case 8: return launch_select_g<8>(sa, n_inst, st);
     }
-    set_error("group size not built (1, 2, 4, 8)");
+    set_error("group size not built (1 to 8)");
     return TRI_ERR_UNSUPPORTED;
 }
 

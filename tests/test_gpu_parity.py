@@ -185,3 +185,12 @@ def test_paged_blocks_of_eight(oracle, pairs):
                 w[name] = np.ascontiguousarray(np.concatenate([x[..., 0::2], x[..., 1::2]], axis=-1))
 
     run_and_check(oracle, cfg, paged=True, inplace=True, pairs=pairs, mutate=mutate)
+
+
+@pytest.mark.parametrize("group", [3, 5, 6, 7])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_group_sizes_that_are_not_powers_of_two(oracle, group, dtype):
+    """G = 3, 5, 6, 7 query heads per KV head (for instance 28 query heads over 4 KV heads)."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=2, n_q_heads=2 * group, n_kv_heads=2, seq_len=520,
+                        min_seq_len=200, budget=77, n_calib=128, dtype=dtype)
+    run_and_check(oracle, cfg)
