@@ -133,3 +133,68 @@ def test_c5_long(oracle):
     """Config 5: 64 layers, G = 8, N = 131072, B = 4096, 32 offsets (up to 2^31), 5 % x10 outliers."""
     cfg = recipe.CONFIGS["c5_long"]
     run_full(oracle, cfg, [(41, 0, 5)])
+
+
+def test_steady_state_ordered(oracle):
+    """The steady-state cadence (Section 4.3): 36 x 64 x 8 head-instances of B + 128 = 2176 keys, ordered compaction."""
+    cfg = recipe.CONFIGS["steady_state"]
+    run_full(oracle, cfg, [(0, 0, 0), (20, 33, 5), (35, 63, 7)])
+
+
+def test_steady_state_minimal_move(oracle):
+    """The same workload evicted in place with the fewest moves (tri_compress_step with dst = NULL): every
+    head-instance is checked by property (the first B slots hold exactly the kept keys, each with its own V row and
+    position; nothing at or beyond slot B changed), sampled ones against the oracle's compact_fill bit for bit."""
+    from paper_2604_04921_amd import binding as T
+    cfg = recipe.CONFIGS["steady_state"]
+    L, S, Hq, Hkv, B, d, G, N = (cfg.n_layers, cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads, cfg.budget, cfg.head_dim,
+                                 cfg.group, cfg.seq_len)
+    w = device.generate(cfg)
+    dev = "cuda"
+    model = T.Model(L, Hq, Hkv, d, cfg.rope_theta, cfg.offsets)
+    cache = T.Cache(w["k"], w["v"], w["pos"], w["seq_len"], w["cur_pos"], N)
+    centers = torch.empty((L, Hq, d // 2, 3), dtype=torch.float32, device=dev)
+    T.tri_build_centers(model, w["q_samples"], centers)
+    kept_idx = torch.full((L, S, Hkv, B), -1, dtype=torch.int32, device=dev)
+    kept_cnt = torch.full((L, S, Hkv), -1, dtype=torch.int32, device=dev)
+    new_len = torch.full((S,), -1, dtype=torch.int32, device=dev)
+    ws = torch.empty(T.tri_workspace_size(model, cache, B), dtype=torch.uint8, device=dev)
+    k0, v0, p0 = w["k"].clone(), w["v"].clone(), w["pos"].clone()
+    assert bool((w["seq_len"] == N).all())
+    T.tri_compress_step(model, centers, cache, None, B, kept_idx, kept_cnt, new_len, ws)
+    torch.cuda.synchronize()
+    assert bool((kept_cnt == B).all()) and bool((new_len == B).all())
+    # nothing at or beyond slot B was written
+    assert torch.equal(w["k"][..., B:, :].view(torch.int16), k0[..., B:, :].view(torch.int16))
+    assert torch.equal(w["v"][..., B:, :].view(torch.int16), v0[..., B:, :].view(torch.int16))
+    assert torch.equal(w["pos"][..., B:], p0[..., B:])
+    moved = 0
+    for l in range(L):   # positions are unique within a head-instance: they identify the keys
+        gi = kept_idx[l].long()
+        want_pos = torch.gather(p0[l], 2, gi)
+        got_pos = w["pos"][l, :, :, :B]
+        oa, ob = torch.argsort(got_pos, dim=2), torch.argsort(want_pos, dim=2)
+        assert torch.equal(torch.gather(got_pos, 2, oa), torch.gather(want_pos, 2, ob))
+        for now, before in ((w["k"], k0), (w["v"], v0)):
+            got = torch.gather(now[l, :, :, :B].view(torch.int16), 2, oa.unsqueeze(-1).expand(-1, -1, -1, d))
+            src_slot = torch.gather(gi, 2, ob)
+            want = torch.gather(before[l].view(torch.int16), 2, src_slot.unsqueeze(-1).expand(-1, -1, -1, d))
+            assert torch.equal(got, want)
+        moved += int((got_pos != p0[l, :, :, :B]).sum())
+    assert moved <= L * S * Hkv * (N - B)      # at most one move per evicted slot below B
+    stats = centers.cpu().numpy()
+    same = 0
+    for (l, s, h) in [(0, 0, 0), (20, 33, 5), (35, 63, 7)]:
+        kn, vn, pn = H.to_numpy(k0[l, s, h]), H.to_numpy(v0[l, s, h]), p0[l, s, h].cpu().numpy()
+        ref = oracle.head_instance(stats[l, h * G:(h + 1) * G], kn, pn, int(w["cur_pos"][s]), cfg.rope_theta, cfg.offsets,
+                                   B, threads=16)
+        got = kept_idx[l, s, h].cpu().numpy()
+        same += H.check_kept(got, B, ref["final"], ref["idx"], N, B)
+        for now, before in ((w["k"], kn), (w["v"], vn), (w["pos"], pn.reshape(N, 1))):
+            exp = np.ascontiguousarray(before).copy()
+            oracle.compact_fill(exp, got)
+            np.testing.assert_array_equal(H.to_numpy(now[l, s, h]).reshape(exp.shape), exp)
+    print("\n[steady_state, minimal-move] %d head-instances checked by property, %d slots moved (%.1f per instance), "
+          "3 by the oracle (%d identical index sets)" % (L * S * Hkv, moved, moved / (L * S * Hkv), same), flush=True)
+    del w, ws, k0, v0, p0
+    torch.cuda.empty_cache()
