@@ -94,7 +94,8 @@ typedef struct tri_cache {
     int32_t n_seqs;               /* S */
     const int32_t *seq_len;       /* device [S]: N_s, number of occupied slots          */
     const int32_t *cur_pos;       /* device [S]: p_q, position of the current query      */
-    int32_t max_seq_len;          /* host upper bound on every N_s (sizes grids and the N stride of score arrays) */
+    int32_t max_seq_len;          /* host upper bound on every N_s (sizes grids and the N stride of score arrays);
+                                     a seq_len entry outside [0, max_seq_len] is read as the nearer bound */
     int32_t block_size;           /* 0 = contiguous */
     const int32_t *block_table;   /* device [S][max_blocks_per_seq], paged only           */
     int32_t max_blocks_per_seq;

@@ -32,6 +32,10 @@ struct CacheView {
     int32_t k_rotated;     // keys stored post-RoPE: no rotation in the score kernel
 };
 
+// A sequence length as read from device memory, forced into [0, max_seq_len]: grids, score-array strides and
+// workspace areas are sized by the host's max_seq_len, so a larger value must never reach an index.
+__device__ __forceinline__ int clamp_len(int n, int max_seq_len) { return min(max(n, 0), max_seq_len); }
+
 // Element offset of slot n of (layer, seq, head) in k / v.
 __device__ __forceinline__ int64_t kv_offset(const CacheView &c, int l, int s, int h, int n)
 {

@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kScoreTile) void score_kernel(ScoreArgs a)
     const int tile = blockIdx.x;
     const int s = blockIdx.y / c.n_kv_heads, h = blockIdx.y % c.n_kv_heads;
     const int l = blockIdx.z;
-    const int N = c.seq_len[s];
+    const int N = clamp_len(c.seq_len[s], c.max_seq_len);
     const int n0 = tile * kScoreTile;
     if (n0 >= N) return;
     const int n = n0 + tid;
@@ -228,7 +228,7 @@ struct StatsArgs {
     const double *partials;
     double *stats;  // [inst][G][2] = (mean, 1/sigma)
     const int32_t *seq_len;
-    int32_t n_seqs, n_kv_heads, n_tiles, G, tile_keys;
+    int32_t n_seqs, n_kv_heads, n_tiles, G, tile_keys, max_seq_len;
 };
 
 // grid (instances), block 256: Section 4.3, mu_g and sigma_g over the N keys (population sigma).
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256) void stats_kernel(StatsArgs a)
     __shared__ double part[16][16];
     const int inst = blockIdx.x;
     const int s = (inst / a.n_kv_heads) % a.n_seqs;
-    const int N = a.seq_len[s];
+    const int N = clamp_len(a.seq_len[s], a.max_seq_len);
     const int tiles = (N + a.tile_keys - 1) / a.tile_keys;
     const int i = threadIdx.x & 15, r = threadIdx.x >> 4;
     const int W = 2 * a.G;
@@ -280,7 +280,7 @@ __global__ __launch_bounds__(256) void final_kernel(FinalArgs a)
 {
     const int inst = blockIdx.y;
     const int s = (inst / a.n_kv_heads) % a.n_seqs;
-    const int N = a.seq_len[s];
+    const int N = clamp_len(a.seq_len[s], a.max_seq_len);
     const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (n >= N) return;
     const float *rw = a.raw + (int64_t)inst * G * a.max_seq_len + n;
@@ -356,7 +356,7 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
     if (timed) (void)hipEventRecord(ev1, st);
     if (rc != TRI_OK) return rc;
     StatsArgs ta{sa.partials, const_cast<double *>(fa.stats), c.seq_len, c.n_seqs, m.n_kv_heads, sa.n_tiles, G,
-                 tile_keys};
+                 tile_keys, c.max_seq_len};
     hipLaunchKernelGGL(stats_kernel, dim3(n_inst), dim3(256), 0, st, ta);
     if ((rc = hip_status("stats_kernel")) != TRI_OK) return rc;
     if (final_out) {

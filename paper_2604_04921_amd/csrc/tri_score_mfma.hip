@@ -151,7 +151,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     const int chunk = (blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x;
     const int s = blockIdx.y / c.n_kv_heads, h = blockIdx.y % c.n_kv_heads;
     const int l = blockIdx.z;
-    const int N = c.seq_len[s];
+    const int N = clamp_len(c.seq_len[s], c.max_seq_len);
     if (chunk * kFastChunk >= N) return;   // uniform over the workgroup
 
     const int64_t inst = ((int64_t)l * c.n_seqs + s) * c.n_kv_heads + h;

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int inst = blockIdx.x;
     const int s = (inst / a.n_kv_heads) % a.n_seqs;
-    const int N = a.seq_len[s];
+    const int N = clamp_len(a.seq_len[s], a.max_seq_len);
     const int B = a.budget;
     int32_t *out = a.kept_idx + (int64_t)inst * B;
     if (tid == 0) a.kept_cnt[inst] = N < B ? N : B;
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int inst = blockIdx.x;
     const int s = (inst / a.n_kv_heads) % a.n_seqs;
-    const int N = a.seq_len[s];
+    const int N = clamp_len(a.seq_len[s], a.max_seq_len);
     const int B = a.budget;
     int32_t *out = a.kept_idx + (int64_t)inst * B;
     if (tid == 0) a.kept_cnt[inst] = N < B ? N : B;

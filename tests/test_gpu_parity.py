@@ -194,3 +194,25 @@ def test_group_sizes_that_are_not_powers_of_two(oracle, group, dtype):
     cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=2, n_q_heads=2 * group, n_kv_heads=2, seq_len=520,
                         min_seq_len=200, budget=77, n_calib=128, dtype=dtype)
     run_and_check(oracle, cfg)
+
+
+def test_sequence_lengths_outside_the_host_bound_are_clamped():
+    """seq_len lives in device memory, so the host cannot check it: an entry above max_seq_len is read as max_seq_len
+    and a negative one as 0 (nothing is indexed beyond what the host sized)."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=2, n_q_heads=8, n_kv_heads=2, seq_len=600,
+                        min_seq_len=600, budget=100, n_calib=128)
+    w = recipe.generate(cfg)
+    outs = []
+    for lens in ([600, 0], [600 + 4321, -7]):
+        w2 = dict(w)
+        w2["seq_len"] = np.array(lens, dtype=np.int32)
+        run = H.GpuRun(cfg, w2)
+        run.build_centers()
+        run.B.tri_compress_step(run.model, run.centers, run.cache, run.cache, cfg.budget, run.kept_idx, run.kept_cnt,
+                                run.new_len, run.ws)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (run.kept_idx, run.kept_cnt, run.new_len, run.k.view(torch.int16),
+                                         run.v.view(torch.int16), run.pos)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    assert outs[0][2].tolist() == [100, 0]
