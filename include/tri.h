@@ -184,6 +184,9 @@ tri_status tri_select_topk(const tri_model *model, const float *final_scores,
  * dst is a different cache it must not overlap src.  dst uses its own strides / block table
  * and src's n_seqs and dtype; dst->seq_len, cur_pos and max_seq_len are ignored.
  *   new_seq_len  NULL or device [n_seqs] int32 <- min(N_s, budget)
+ * kept_idx must be ascending and free of duplicates per head-instance (as tri_select_topk writes it);
+ * otherwise the result is unspecified, but a count is read into [0, budget] and a slot index into
+ * [0, src->max_seq_len - 1], so no memory outside the caches is touched.
  */
 tri_status tri_compact(const tri_model *model, const tri_cache *src, const tri_cache *dst,
                        int32_t budget, const int32_t *kept_idx, const int32_t *kept_cnt,

@@ -28,6 +28,14 @@ __device__ __forceinline__ void write_new_len(const CompactArgs &a, int l, int s
     if (a.new_seq_len && l == 0 && h == 0 && threadIdx.x == 0) a.new_seq_len[s] = cnt;
 }
 
+// kept_cnt and kept_idx live in device memory where the host cannot check them: a count is read into
+// [0, budget] and a slot index into [0, max_seq_len - 1], so that nothing outside the caches is touched.
+__device__ __forceinline__ int read_cnt(const CompactArgs &a, int inst) { return min(max(a.kept_cnt[inst], 0), a.budget); }
+__device__ __forceinline__ int read_slot(const CompactArgs &a, const int32_t *idx, int j)
+{
+    return min(max(idx[j], 0), a.src.max_seq_len - 1);
+}
+
 constexpr int kRowsPerBlock = 64;
 
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
@@ -45,7 +53,7 @@ __global__ __launch_bounds__(256) void gather_kernel(CompactArgs a)
     const int inst = blockIdx.y;
     int l, s, h;
     decode_inst(a.src, inst, l, s, h);
-    const int cnt = a.kept_cnt[inst];
+    const int cnt = read_cnt(a, inst);
     if (blockIdx.x == 0) write_new_len(a, l, s, h, cnt);
     const int rows_per_pass = 256 / a.row16;
     const int r = threadIdx.x / a.row16, part = threadIdx.x % a.row16;
@@ -55,7 +63,7 @@ __global__ __launch_bounds__(256) void gather_kernel(CompactArgs a)
     for (int j0 = blockIdx.x * kRowsPerBlock; j0 < (blockIdx.x + 1) * kRowsPerBlock; j0 += rows_per_pass) {
         const int j = j0 + r;
         if (j >= cnt) continue;
-        const int n = idx[j];
+        const int n = read_slot(a, idx, j);
         const int64_t so = kv_offset(a.src, l, s, h, n) * a.elem_bytes + part * 16;
         const int64_t d_o = kv_offset(a.dst, l, s, h, j) * a.elem_bytes + part * 16;
         const uint4 kv = load_stream16(sk + so);
@@ -79,7 +87,7 @@ __global__ __launch_bounds__(kInplaceThreads) void inplace_kernel(CompactArgs a)
     const int inst = blockIdx.x;
     int l, s, h;
     decode_inst(a.src, inst, l, s, h);
-    const int cnt = a.kept_cnt[inst];
+    const int cnt = read_cnt(a, inst);
     write_new_len(a, l, s, h, cnt);
     const int rows_per_pass = kInplaceThreads / a.row16;
     const int r = threadIdx.x / a.row16, part = threadIdx.x % a.row16;
@@ -93,7 +101,7 @@ __global__ __launch_bounds__(kInplaceThreads) void inplace_kernel(CompactArgs a)
 #pragma unroll
         for (int u = 0; u < kInplaceUnroll; ++u) {
             const int j = j0 + u * rows_per_pass + r;
-            src_n[u] = j < cnt ? idx[j] : -1;
+            src_n[u] = j < cnt ? read_slot(a, idx, j) : -1;
         }
 #pragma unroll
         for (int u = 0; u < kInplaceUnroll; ++u) {
@@ -139,7 +147,7 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(CompactArgs a)
     const int inst = blockIdx.x;
     int l, s, h;
     decode_inst(a.src, inst, l, s, h);
-    const int cnt = a.kept_cnt[inst];
+    const int cnt = read_cnt(a, inst);
     write_new_len(a, l, s, h, cnt);
     const int32_t *idx = a.kept_idx + (int64_t)inst * a.budget;
     const int n_words = (cnt + 31) >> 5;
@@ -148,7 +156,7 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(CompactArgs a)
     __syncthreads();
     int my_tail = 0;
     for (int j = tid; j < cnt; j += kFillThreads) {
-        const int n = idx[j];
+        const int n = read_slot(a, idx, j);
         if (n < cnt) atomicOr(&kept_bits[n >> 5], 1u << (n & 31));
         else ++my_tail;
     }
@@ -182,11 +190,13 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(CompactArgs a)
         while (free_bits) {
             const int bit = __ffs(free_bits) - 1;
             free_bits &= free_bits - 1u;
-            moves[o] = (w << 5) + bit;
-            moves[a.budget + o] = idx[first_tail + o];
+            if (o < n_tail) {   // always true for an ascending duplicate-free kept_idx; guards the reads otherwise
+                moves[o] = (w << 5) + bit;
+                moves[a.budget + o] = read_slot(a, idx, first_tail + o);
+            }
             ++o;
         }
-        done += (int)total;
+        done = min(done + (int)total, n_tail);
         __syncthreads();
     }
     // done == n_tail moves; 16 bytes of K and of V per thread and move
