@@ -44,7 +44,10 @@ __device__ __forceinline__ void store_stream16(char *p, const uint4 &v)
     __builtin_nontemporal_store(uint4v{v.x, v.y, v.z, v.w}, reinterpret_cast<uint4v *>(p));
 }
 
-constexpr int kRowsPerBlock = 16;   // one pass of a 256-thread workgroup over bf16 rows (measured best of 16 / 64 / 256)
+// 128 threads, one pass over 8 bf16 rows: small workgroups keep the most independent row fetches in flight
+// (measured on 9.4 M scattered rows: 64 threads 1.64 ms, 128: 1.63, 256: 1.71, 512: 1.68, 1024: 1.72)
+constexpr int kGatherThreads = 128;
+constexpr int kRowsPerBlock = kGatherThreads / 16;
 
 
 // the evicted cache is read once: non-temporal hint (a streaming read is 13 % faster with it on this GPU)
@@ -54,15 +57,15 @@ __device__ __forceinline__ uint4 load_stream16(const char *p)
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-// dst and src are different memory: a plain gather.  grid (ceil(B/64), instances), block 256.
-__global__ __launch_bounds__(256) void gather_kernel(CompactArgs a)
+// dst and src are different memory: a plain gather.  grid (ceil(B/8), instances), block 128.
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(CompactArgs a)
 {
     const int inst = blockIdx.y;
     int l, s, h;
     decode_inst(a.src, inst, l, s, h);
     const int cnt = read_cnt(a, inst);
     if (blockIdx.x == 0) write_new_len(a, l, s, h, cnt);
-    const int rows_per_pass = 256 / a.row16;
+    const int rows_per_pass = kGatherThreads / a.row16;
     const int r = threadIdx.x / a.row16, part = threadIdx.x % a.row16;
     const int32_t *idx = a.kept_idx + (int64_t)inst * a.budget;
     const char *sk = (const char *)a.src.k, *sv = (const char *)a.src.v;
@@ -274,7 +277,7 @@ tri_status launch_compact(const tri_model &m, const tri_cache &src, const tri_ca
         hipLaunchKernelGGL(inplace_kernel, dim3(n_inst), dim3(kInplaceThreads), 0, st, a);
         return hip_status("inplace_kernel");
     }
-    hipLaunchKernelGGL(gather_kernel, dim3((budget + kRowsPerBlock - 1) / kRowsPerBlock, n_inst), dim3(256), 0,
+    hipLaunchKernelGGL(gather_kernel, dim3((budget + kRowsPerBlock - 1) / kRowsPerBlock, n_inst), dim3(kGatherThreads), 0,
                        st, a);
     return hip_status("gather_kernel");
 }
