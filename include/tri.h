@@ -73,6 +73,11 @@ typedef struct tri_model {
     int32_t n_offsets;      /* |D| >= 1 */
     const int64_t *offsets; /* HOST array [n_offsets] */
     int32_t score_variant;  /* tri_score_variant; 0 = the method */
+    const int32_t *head_budgets; /* NULL: every head-instance keeps `budget` keys (the paper's setting).  Else DEVICE
+                               [n_layers][n_kv_heads]: the budget of each (layer, KV head), read into [0, budget]
+                               (head-specific budgets, named as future work in Appendix A).  `budget` stays the
+                               stride of kept_idx; kept_cnt holds min(N_s, the head's budget); new_seq_len
+                               then reports layer 0, head 0 only */
 } tri_model;
 
 /*

@@ -24,7 +24,8 @@ EXPORTS = ["tri_last_error", "tri_build_centers", "tri_centers_accumulate", "tri
 class TriModel(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("rope_theta", ctypes.c_double), ("pairs", ctypes.c_int32),
-                ("n_offsets", ctypes.c_int32), ("offsets", ctypes.c_void_p), ("score_variant", ctypes.c_int32)]
+                ("n_offsets", ctypes.c_int32), ("offsets", ctypes.c_void_p), ("score_variant", ctypes.c_int32),
+                ("head_budgets", ctypes.c_void_p)]
 
 
 class TriCache(ctypes.Structure):
@@ -116,10 +117,15 @@ class Model:
     """Host-side tri_model; keeps the offsets array alive."""
 
     def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, rope_theta, offsets, pairs=TRI_PAIR_INTERLEAVED,
-                 score_variant=TRI_SCORE_FULL):
+                 score_variant=TRI_SCORE_FULL, head_budgets=None):
         self._offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+        self._head_budgets = head_budgets   # device int32 [n_layers][n_kv_heads] or None; kept alive here
+        if head_budgets is not None:
+            assert head_budgets.dtype == torch.int32 and head_budgets.is_contiguous()
+            assert tuple(head_budgets.shape) == (n_layers, n_kv_heads)
         self.c = TriModel(n_layers, n_q_heads, n_kv_heads, head_dim, float(rope_theta), pairs, len(self._offsets),
-                          self._offsets.ctypes.data_as(ctypes.c_void_p), int(score_variant))
+                          self._offsets.ctypes.data_as(ctypes.c_void_p), int(score_variant),
+                          None if head_budgets is None else head_budgets.data_ptr())
 
     @property
     def ref(self):

@@ -34,7 +34,16 @@ struct SelectArgs {
     int32_t *kept_idx;     // [inst][B]
     int32_t *kept_cnt;     // [inst]
     int32_t n_seqs, n_kv_heads, max_seq_len, budget, lds_keys;
+    const int32_t *head_budgets;   // [L][Hkv] or NULL: budget of each (layer, KV head), at most `budget`
 };
+
+// The budget of head-instance `inst`: the common one, or the head's own (read into [0, budget]).
+__device__ __forceinline__ int instance_budget(const SelectArgs &a, int inst)
+{
+    if (!a.head_budgets) return a.budget;
+    const int h = inst % a.n_kv_heads, l = inst / (a.n_kv_heads * a.n_seqs);
+    return min(max(a.head_budgets[l * a.n_kv_heads + h], 0), a.budget);
+}
 
 // grid (instances), block 1024.  G = 0: final scores given; G > 0: raw scores of G query heads given.
 template <int G>
@@ -50,9 +59,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
     const int inst = blockIdx.x;
     const int s = (inst / a.n_kv_heads) % a.n_seqs;
     const int N = clamp_len(a.seq_len[s], a.max_seq_len);
-    const int B = a.budget;
-    int32_t *out = a.kept_idx + (int64_t)inst * B;
+    const int B = instance_budget(a, inst);
+    int32_t *out = a.kept_idx + (int64_t)inst * a.budget;
     if (tid == 0) a.kept_cnt[inst] = N < B ? N : B;
+    if (B == 0) return;   // a head whose own budget is 0 keeps nothing
     if (N <= B) {  // nothing to evict: keep every slot
         for (int n = tid; n < N; n += kSelThreads) out[n] = n;
         return;
@@ -218,9 +228,10 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
     const int inst = blockIdx.x;
     const int s = (inst / a.n_kv_heads) % a.n_seqs;
     const int N = clamp_len(a.seq_len[s], a.max_seq_len);
-    const int B = a.budget;
-    int32_t *out = a.kept_idx + (int64_t)inst * B;
+    const int B = instance_budget(a, inst);
+    int32_t *out = a.kept_idx + (int64_t)inst * a.budget;
     if (tid == 0) a.kept_cnt[inst] = N < B ? N : B;
+    if (B == 0) return;   // a head whose own budget is 0 keeps nothing
     if (N <= B) {  // nothing to evict: keep every slot
         for (int n = tid; n < N; n += THREADS) out[n] = n;
         return;
@@ -446,7 +457,8 @@ tri_status launch_select(const tri_model &m, const float *final_scores, const fl
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
     if (n_inst <= 0) return TRI_OK;
     SelectArgs sa{final_scores, raw, stats, scratch, c.seq_len, kept_idx, kept_cnt, c.n_seqs, m.n_kv_heads,
-                  c.max_seq_len, budget, c.max_seq_len < kSelLdsKeys ? (c.max_seq_len > 0 ? c.max_seq_len : 1) : kSelLdsKeys};
+                  c.max_seq_len, budget, c.max_seq_len < kSelLdsKeys ? (c.max_seq_len > 0 ? c.max_seq_len : 1) : kSelLdsKeys,
+                  m.head_budgets};
     if (final_scores) return launch_select_g<0>(sa, n_inst, st);
     switch (m.n_q_heads / m.n_kv_heads) {
         case 1: return launch_select_g<1>(sa, n_inst, st);

@@ -27,13 +27,14 @@ def to_numpy(t):
 class GpuRun:
     """One workload resident on the GPU with the buffers the four entry points need."""
 
-    def __init__(self, cfg, w, paged=False, pairs=0, variant=0, rotated=False):
+    def __init__(self, cfg, w, paged=False, pairs=0, variant=0, rotated=False, head_budgets=None):
         from paper_2604_04921_amd import binding as B
         self.B = B
         self.cfg = cfg
         dev = "cuda"
         self.model = B.Model(cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.rope_theta, cfg.offsets,
-                             pairs, variant)
+                             pairs, variant,
+                             None if head_budgets is None else torch.from_numpy(np.ascontiguousarray(head_budgets, np.int32)).cuda())
         self.q = to_torch(w["q_samples"], cfg.dtype)
         self.seq_len = torch.from_numpy(w["seq_len"]).to(dev)
         self.cur_pos = torch.from_numpy(w["cur_pos"]).to(dev)
