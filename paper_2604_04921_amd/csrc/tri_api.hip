@@ -162,6 +162,8 @@ Workspace workspace_layout(const tri_model &m, const tri_cache &c, int32_t budge
     size_t o = 0;
     w.band_rev = o;
     o = align256(o + kBands * sizeof(double));
+    w.fold_phasors = o;
+    o = align256(o + ((size_t)c.n_seqs + 1) * kBands * 2 * sizeof(double));
     w.phasors = o;
     o = align256(o + 128 * 1024);
     w.table = o;

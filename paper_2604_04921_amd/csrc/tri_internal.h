@@ -57,6 +57,7 @@ __device__ __forceinline__ int64_t pos_offset(const CacheView &c, int l, int s, 
 // Workspace carve-up (all offsets 256-byte aligned).
 struct Workspace {
     size_t band_rev;   // double [F]: omega_f / 2pi
+    size_t fold_phasors;   // double [1 + S][F][2]: mean over the offsets of e^{i w delta}; e^{i w cur_pos[s]}
     size_t phasors;    // relative-position phasor table of the MFMA score kernel
     size_t table;      // float  [L][S][Hkv][F][3][G]: folded centre table
     size_t partials;   // double [L][S][Hkv][n_tiles][2G]: per-tile sum and sum of squares

@@ -21,6 +21,7 @@ struct FoldArgs {
     const float *centers;   // [L][Hq][F][3]
     float *table;           // [L][S][Hkv][F][3][G]
     double *band_rev;       // [F]
+    double *phasors;        // [1 + S][F][2]: (0) mean over the offsets of e^{i w delta}; (1 + s) e^{i w cur_pos[s]}
     const int32_t *cur_pos; // [S]
     int32_t S, Hq, Hkv, G;
     double theta;
@@ -37,24 +38,41 @@ __device__ __forceinline__ void unit_phasor(double t, double rev, double *c, dou
     sincos(kTwoPi * x, s, c);
 }
 
+// The phasors the fold needs depend on the band and, for the query position, on the sequence only: they
+// are evaluated once here (double-precision pow / sincos are long software routines) instead of once per
+// query head and layer.  grid (1 + S), block F: thread = band.
+__global__ __launch_bounds__(kBands) void fold_phasor_kernel(FoldArgs a)
+{
+    const int f = threadIdx.x;
+    // Section 2.1: omega_f = theta^(-2f/d); kept as revolutions per position
+    const double rev = pow(a.theta, -2.0 * (double)f / (double)kHeadDim) / kTwoPi;
+    double *out = a.phasors + ((int64_t)blockIdx.x * kBands + f) * 2;
+    if (blockIdx.x == 0) {
+        a.band_rev[f] = rev;
+        double er = 0.0, ei = 0.0;
+        for (int j = 0; j < a.n_off; ++j) {
+            double c, s;
+            unit_phasor((double)a.offsets[j], rev, &c, &s);
+            er += c;
+            ei += s;
+        }
+        out[0] = er / (double)a.n_off;
+        out[1] = ei / (double)a.n_off;
+    } else {
+        double c, s;
+        unit_phasor((double)a.cur_pos[blockIdx.x - 1], rev, &c, &s);
+        out[0] = c;
+        out[1] = s;
+    }
+}
+
 constexpr int kFoldSeqs = 8;   // sequences per workgroup
 
 // grid (Hq, L, ceil(S / kFoldSeqs)), block F: thread = band
 __global__ __launch_bounds__(kBands) void fold_kernel(FoldArgs a)
 {
     const int f = threadIdx.x, qh = blockIdx.x, l = blockIdx.y;
-    // Section 2.1: omega_f = theta^(-2f/d); kept as revolutions per position
-    const double rev = pow(a.theta, -2.0 * (double)f / (double)kHeadDim) / kTwoPi;
-    if (qh == 0 && l == 0 && blockIdx.z == 0) a.band_rev[f] = rev;
-    double er = 0.0, ei = 0.0;
-    for (int j = 0; j < a.n_off; ++j) {
-        double c, s;
-        unit_phasor((double)a.offsets[j], rev, &c, &s);
-        er += c;
-        ei += s;
-    }
-    er /= (double)a.n_off;
-    ei /= (double)a.n_off;
+    const double er = a.phasors[f * 2], ei = a.phasors[f * 2 + 1];
     const float *ct = a.centers + (((int64_t)l * a.Hq + qh) * kBands + f) * 3;
     const double qr = (double)ct[0], qi = (double)ct[1], qa = (double)ct[2];
     // the ablation variants (Section 5) only change the table: no trig part, no norm part, or the norm
@@ -65,8 +83,7 @@ __global__ __launch_bounds__(kBands) void fold_kernel(FoldArgs a)
     const int h = qh / a.G, g = qh % a.G;
     const int s_end = min(a.S, ((int)blockIdx.z + 1) * kFoldSeqs);
     for (int s = blockIdx.z * kFoldSeqs; s < s_end; ++s) {
-        double c, sn;
-        unit_phasor((double)a.cur_pos[s], rev, &c, &sn);
+        const double c = a.phasors[((int64_t)(1 + s) * kBands + f) * 2], sn = a.phasors[((int64_t)(1 + s) * kBands + f) * 2 + 1];
         float *t = a.table + (((((int64_t)l * a.S + s) * a.Hkv + h) * kBands + f) * 3) * a.G;
         t[0 * a.G + g] = (float)(ar * c - ai * sn);
         t[1 * a.G + g] = (float)(ar * sn + ai * c);
@@ -377,6 +394,7 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     fo.centers = centers;
     fo.table = reinterpret_cast<float *>(ws + wl.table);
     fo.band_rev = reinterpret_cast<double *>(ws + wl.band_rev);
+    fo.phasors = reinterpret_cast<double *>(ws + wl.fold_phasors);
     fo.cur_pos = c.cur_pos;
     fo.S = c.n_seqs;
     fo.Hq = m.n_q_heads;
@@ -386,6 +404,9 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     fo.n_off = m.n_offsets;
     fo.variant = m.score_variant;
     for (int j = 0; j < m.n_offsets; ++j) fo.offsets[j] = m.offsets[j];
+    hipLaunchKernelGGL(fold_phasor_kernel, dim3(1 + c.n_seqs), dim3(kBands), 0, st, fo);
+    tri_status rc0 = hip_status("fold_phasor_kernel");
+    if (rc0 != TRI_OK) return rc0;
     hipLaunchKernelGGL(fold_kernel, dim3(m.n_q_heads, m.n_layers, (c.n_seqs + kFoldSeqs - 1) / kFoldSeqs), dim3(kBands), 0,
                        st, fo);
     tri_status rc = hip_status("fold_kernel");
