@@ -68,10 +68,12 @@ __global__ __launch_bounds__(kBands) void fold_phasor_kernel(FoldArgs a)
 
 constexpr int kFoldSeqs = 8;   // sequences per workgroup
 
-// grid (Hq, L, ceil(S / kFoldSeqs)), block F: thread = band
-__global__ __launch_bounds__(kBands) void fold_kernel(FoldArgs a)
+// grid (Hkv, L, ceil(S / kFoldSeqs)), block F * G: thread = (band, query head of the group), so that a
+// wave's stores fill whole stretches of the [F][3][G] table of its head-instance
+__global__ __launch_bounds__(kBands *kMaxGroup) void fold_kernel(FoldArgs a)
 {
-    const int f = threadIdx.x, qh = blockIdx.x, l = blockIdx.y;
+    const int f = threadIdx.x / a.G, g = threadIdx.x % a.G, h = blockIdx.x, l = blockIdx.y;
+    const int qh = h * a.G + g;
     const double er = a.phasors[f * 2], ei = a.phasors[f * 2 + 1];
     const float *ct = a.centers + (((int64_t)l * a.Hq + qh) * kBands + f) * 3;
     const double qr = (double)ct[0], qi = (double)ct[1], qa = (double)ct[2];
@@ -80,7 +82,6 @@ __global__ __launch_bounds__(kBands) void fold_kernel(FoldArgs a)
     const bool trig_on = a.variant != TRI_SCORE_NORM_ONLY, norm_on = a.variant != TRI_SCORE_TRIG_ONLY;
     const double ar = trig_on ? qr * er - qi * ei : 0.0, ai = trig_on ? qr * ei + qi * er : 0.0;
     const double cn = !norm_on ? 0.0 : a.variant == TRI_SCORE_NORM_UNWEIGHTED ? qa : qa - hypot(qr, qi);
-    const int h = qh / a.G, g = qh % a.G;
     const int s_end = min(a.S, ((int)blockIdx.z + 1) * kFoldSeqs);
     for (int s = blockIdx.z * kFoldSeqs; s < s_end; ++s) {
         const double c = a.phasors[((int64_t)(1 + s) * kBands + f) * 2], sn = a.phasors[((int64_t)(1 + s) * kBands + f) * 2 + 1];
@@ -407,8 +408,8 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     hipLaunchKernelGGL(fold_phasor_kernel, dim3(1 + c.n_seqs), dim3(kBands), 0, st, fo);
     tri_status rc0 = hip_status("fold_phasor_kernel");
     if (rc0 != TRI_OK) return rc0;
-    hipLaunchKernelGGL(fold_kernel, dim3(m.n_q_heads, m.n_layers, (c.n_seqs + kFoldSeqs - 1) / kFoldSeqs), dim3(kBands), 0,
-                       st, fo);
+    hipLaunchKernelGGL(fold_kernel, dim3(m.n_kv_heads, m.n_layers, (c.n_seqs + kFoldSeqs - 1) / kFoldSeqs),
+                       dim3(kBands * G), 0, st, fo);
     tri_status rc = hip_status("fold_kernel");
     if (rc != TRI_OK) return rc;
 
