@@ -167,7 +167,7 @@ def test_post_rope_cache(oracle, dtype, pairs, paged):
             for name in ("k", "q_samples"):
                 x = w[name]
                 w[name] = np.ascontiguousarray(np.concatenate([x[..., 0::2], x[..., 1::2]], axis=-1))
-        w["k"] = recipe.to_post_rope(w["k"], w["pos"], cfg.rope_theta, pairs, cfg.dtype)
+        w["k"] = H.to_post_rope(w["k"], w["pos"], cfg.rope_theta, pairs, cfg.dtype)
 
     run_and_check(oracle, cfg, paged=paged, pairs=pairs, mutate=mutate, rotated=True)
 

@@ -132,3 +132,23 @@ def check_kept(idx, cnt, ref_final, ref_idx, N, B):
     if tau - nxt > GAP_RTOL * max(abs(tau), abs(nxt)):
         assert same, "index set differs although the oracle's gap at the budget is wide"
     return same
+
+
+def to_post_rope(k, pos, theta, pairs, dtype):
+    """Test input: stored keys [..., N, d] (bf16 bits or float32) -> the same keys as a post-RoPE cache holds them: band f of
+    the key in slot n turned by theta^(-2f/d) * pos[..., n] radians (in double), rounded back to the storage
+    type.  pairs: 0 = band f is (x[2f], x[2f+1]), 1 = (x[f], x[f + d/2])."""
+    x = recipe.bf16_bits_to_f32(k).astype(np.float64) if dtype == "bf16" else k.astype(np.float64)
+    d = x.shape[-1]
+    F = d // 2
+    re, im = (x[..., :F], x[..., F:]) if pairs else (x[..., 0::2], x[..., 1::2])
+    ang = pos[..., None].astype(np.float64) * (float(theta) ** (-2.0 * np.arange(F) / d))
+    c, s = np.cos(ang), np.sin(ang)
+    rr, ri = c * re - s * im, s * re + c * im
+    out = np.empty_like(x)
+    if pairs:
+        out[..., :F], out[..., F:] = rr, ri
+    else:
+        out[..., 0::2], out[..., 1::2] = rr, ri
+    out = out.astype(np.float32)
+    return recipe.to_bf16_bits(out) if dtype == "bf16" else out
