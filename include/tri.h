@@ -118,7 +118,7 @@ const char *tri_last_error(void);
  * Offline calibration (Section 4.1 text under both score equations; Appendix B.5): per
  * (layer, query head, band f) the complex mean of the pre-RoPE query samples, E[q_f], and the
  * mean modulus E||q_f||.
- *   q_samples    device [n_tokens][n_layers][n_q_heads][head_dim], q_dtype
+ *   q_samples    device [n_tokens][n_layers][n_q_heads][head_dim], q_dtype, 16-byte aligned
  *   centers_out  device [n_layers][n_q_heads][head_dim/2][3] float = (Re E[q_f], Im E[q_f], E||q_f||)
  * Sums are accumulated in double in a fixed order (deterministic).  n_tokens >= 1.
  */

@@ -222,8 +222,9 @@ tri_status tri_build_centers(const tri_model *model, const void *q_samples, int3
 {
     tri_status rc = check_model(model);
     if (rc != TRI_OK) return rc;
-    if (!q_samples || !centers_out || n_tokens < 1 || (q_dtype != TRI_F32 && q_dtype != TRI_BF16)) {
-        set_error("tri_build_centers: q_samples, centers_out, n_tokens >= 1 and a known dtype required");
+    if (!q_samples || ((uintptr_t)q_samples & 15) || !centers_out || n_tokens < 1 ||
+        (q_dtype != TRI_F32 && q_dtype != TRI_BF16)) {
+        set_error("tri_build_centers: q_samples (16-byte aligned), centers_out, n_tokens >= 1 and a known dtype required");
         return TRI_ERR_INVALID_ARG;
     }
     return launch_centers(*model, q_samples, q_dtype, n_tokens, centers_out, nullptr, 0, (hipStream_t)stream);
@@ -234,8 +235,8 @@ tri_status tri_centers_accumulate(const tri_model *model, const void *q_samples,
 {
     tri_status rc = check_model(model);
     if (rc != TRI_OK) return rc;
-    if (!q_samples || !sums || n_tokens < 1 || (q_dtype != TRI_F32 && q_dtype != TRI_BF16)) {
-        set_error("tri_centers_accumulate: q_samples, sums, n_tokens >= 1 and a known dtype required");
+    if (!q_samples || ((uintptr_t)q_samples & 15) || !sums || n_tokens < 1 || (q_dtype != TRI_F32 && q_dtype != TRI_BF16)) {
+        set_error("tri_centers_accumulate: q_samples (16-byte aligned), sums, n_tokens >= 1 and a known dtype required");
         return TRI_ERR_INVALID_ARG;
     }
     return launch_centers(*model, q_samples, q_dtype, n_tokens, nullptr, sums, first ? 1 : 0, (hipStream_t)stream);

@@ -15,37 +15,93 @@ struct CentersArgs {
     int32_t first;  // sums: 1 = overwrite, 0 = add to what is there
 };
 
-constexpr int kCenterParts = 16;
+constexpr int kCenterThreads = 512;   // 8 band octets x 64 token residues
+constexpr int kCenterWaves = kCenterThreads / 64;
 
-__device__ __forceinline__ double load_q(const CentersArgs &a, int64_t i)
+// The (re, im) of bands 8q..8q+7 of the head vector that starts at element `row`: 32 contiguous bytes (bf16,
+// interleaved pairs), two 16-byte pieces 128 bytes apart (bf16, half-split), or the fp32 counterparts.
+__device__ __forceinline__ void load_octet(const CentersArgs &a, int64_t row, int q, float (&re)[8], float (&im)[8])
 {
-    if (a.is_bf16) return (double)__uint_as_float((uint32_t)((const uint16_t *)a.q)[i] << 16);
-    return (double)((const float *)a.q)[i];
+    const bool half = a.pairs == TRI_PAIR_HALF;
+    if (a.is_bf16) {
+        const uint16_t *p = (const uint16_t *)a.q + row;
+        const uint4 u0 = *reinterpret_cast<const uint4 *>(p + (half ? 8 * q : 16 * q));
+        const uint4 u1 = *reinterpret_cast<const uint4 *>(p + (half ? kBands + 8 * q : 16 * q + 8));
+        const uint32_t w0[4] = {u0.x, u0.y, u0.z, u0.w}, w1[4] = {u1.x, u1.y, u1.z, u1.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (half) {   // u0 = 8 real parts, u1 = 8 imaginary parts
+                re[2 * k] = __uint_as_float(w0[k] << 16);
+                re[2 * k + 1] = __uint_as_float(w0[k] & 0xffff0000u);
+                im[2 * k] = __uint_as_float(w1[k] << 16);
+                im[2 * k + 1] = __uint_as_float(w1[k] & 0xffff0000u);
+            } else {      // u0 = bands 0-3 as (re, im) pairs, u1 = bands 4-7
+                re[k] = __uint_as_float(w0[k] << 16);
+                im[k] = __uint_as_float(w0[k] & 0xffff0000u);
+                re[4 + k] = __uint_as_float(w1[k] << 16);
+                im[4 + k] = __uint_as_float(w1[k] & 0xffff0000u);
+            }
+        }
+    } else {
+        const float *p = (const float *)a.q + row;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (half) {
+                const float4 r4 = *reinterpret_cast<const float4 *>(p + 8 * q + 4 * k);
+                const float4 i4 = *reinterpret_cast<const float4 *>(p + kBands + 8 * q + 4 * k);
+                re[4 * k] = r4.x, re[4 * k + 1] = r4.y, re[4 * k + 2] = r4.z, re[4 * k + 3] = r4.w;
+                im[4 * k] = i4.x, im[4 * k + 1] = i4.y, im[4 * k + 2] = i4.z, im[4 * k + 3] = i4.w;
+            } else {
+                const float4 a4 = *reinterpret_cast<const float4 *>(p + 16 * q + 8 * k);
+                const float4 b4 = *reinterpret_cast<const float4 *>(p + 16 * q + 8 * k + 4);
+                re[4 * k] = a4.x, im[4 * k] = a4.y, re[4 * k + 1] = a4.z, im[4 * k + 1] = a4.w;
+                re[4 * k + 2] = b4.x, im[4 * k + 2] = b4.y, re[4 * k + 3] = b4.z, im[4 * k + 3] = b4.w;
+            }
+        }
+    }
 }
 
-// grid (Hq, L), block F * 16: thread = (band, token residue mod 16); double sums, fixed order.
-__global__ __launch_bounds__(kBands *kCenterParts) void centers_kernel(CentersArgs a)
+// grid (Hq, L), block 512: thread = (token residue r mod 64, band octet q); eight neighbouring threads read one
+// whole head vector with 16-byte loads.  Double sums in a fixed order: per thread over its tokens, then a
+// butterfly over the 8 residues of a wave, then the 8 waves in order.
+__global__ __launch_bounds__(kCenterThreads) void centers_kernel(CentersArgs a)
 {
-    __shared__ double part[kCenterParts][kBands][3];
-    const int f = threadIdx.x % kBands, r = threadIdx.x / kBands;
+    __shared__ double part[kCenterWaves][kBands][3];
+    const int q = threadIdx.x & 7, r = threadIdx.x >> 3, wave = threadIdx.x >> 6;
     const int h = blockIdx.x, l = blockIdx.y;
-    const int ire = a.pairs == TRI_PAIR_HALF ? f : 2 * f;
-    const int iim = a.pairs == TRI_PAIR_HALF ? f + kBands : 2 * f + 1;
-    double sre = 0.0, sim = 0.0, sab = 0.0;
-    for (int64_t t = r; t < a.T; t += kCenterParts) {
-        const int64_t row = ((t * a.L + l) * a.Hq + h) * kHeadDim;
-        const double re = load_q(a, row + ire), im = load_q(a, row + iim);
-        sre += re;
-        sim += im;
-        sab += sqrt(re * re + im * im);
+    double sre[8], sim[8], sab[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) sre[k] = sim[k] = sab[k] = 0.0;
+    for (int64_t t = r; t < a.T; t += kCenterThreads / 8) {
+        float re[8], im[8];
+        load_octet(a, ((t * a.L + l) * a.Hq + h) * kHeadDim, q, re, im);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const double x = (double)re[k], y = (double)im[k];
+            sre[k] += x;
+            sim[k] += y;
+            sab[k] += sqrt(x * x + y * y);
+        }
     }
-    part[r][f][0] = sre;
-    part[r][f][1] = sim;
-    part[r][f][2] = sab;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+#pragma unroll
+        for (int o = 8; o < 64; o <<= 1) {   // lanes that differ in the residue only
+            sre[k] += __shfl_xor(sre[k], o, 64);
+            sim[k] += __shfl_xor(sim[k], o, 64);
+            sab[k] += __shfl_xor(sab[k], o, 64);
+        }
+        if ((threadIdx.x & 63) < 8) {
+            part[wave][8 * q + k][0] = sre[k];
+            part[wave][8 * q + k][1] = sim[k];
+            part[wave][8 * q + k][2] = sab[k];
+        }
+    }
     __syncthreads();
-    if (r == 0) {
+    if (threadIdx.x < kBands) {
+        const int f = threadIdx.x;
         double t0 = 0.0, t1 = 0.0, t2 = 0.0;
-        for (int k = 0; k < kCenterParts; ++k) {
+        for (int k = 0; k < kCenterWaves; ++k) {
             t0 += part[k][f][0];
             t1 += part[k][f][1];
             t2 += part[k][f][2];
@@ -110,7 +166,7 @@ tri_status launch_centers(const tri_model &m, const void *q, int32_t q_dtype, in
                           double *sums, int32_t first, hipStream_t st)
 {
     CentersArgs a{q, out, sums, n_tokens, m.n_layers, m.n_q_heads, m.pairs, q_dtype == TRI_BF16 ? 1 : 0, first};
-    hipLaunchKernelGGL(centers_kernel, dim3(m.n_q_heads, m.n_layers), dim3(kBands * kCenterParts), 0, st, a);
+    hipLaunchKernelGGL(centers_kernel, dim3(m.n_q_heads, m.n_layers), dim3(kCenterThreads), 0, st, a);
     return hip_status("centers_kernel");
 }
 
