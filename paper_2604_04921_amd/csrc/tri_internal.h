@@ -36,6 +36,23 @@ struct CacheView {
 // workspace areas are sized by the host's max_seq_len, so a larger value must never reach an index.
 __device__ __forceinline__ int clamp_len(int n, int max_seq_len) { return min(max(n, 0), max_seq_len); }
 
+// Section 4.3, z-score of one raw score: (s - mu) / sigma with mu held as two floats (the double split into hi + lo)
+// and 1/sigma as one.  Three fp32 operations that agree with the double-precision expression to about two units in
+// the last place (raw - mu_hi is exact when the two are within a factor of two).  Every kernel that forms a final
+// score goes through this one function, so the fused step and tri_score + tri_select_topk agree bit for bit.
+struct ZParams {
+    float mu_hi, mu_lo, rs;
+};
+__device__ __forceinline__ ZParams z_params(double mu, double inv_sigma)
+{
+    ZParams p;
+    p.mu_hi = (float)mu;
+    p.mu_lo = (float)(mu - (double)p.mu_hi);
+    p.rs = (float)inv_sigma;
+    return p;
+}
+__device__ __forceinline__ float z_score(float raw, const ZParams &p) { return ((raw - p.mu_hi) - p.mu_lo) * p.rs; }
+
 // Element offset of slot n of (layer, seq, head) in k / v.
 __device__ __forceinline__ int64_t kv_offset(const CacheView &c, int l, int s, int h, int n)
 {

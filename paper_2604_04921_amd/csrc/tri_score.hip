@@ -308,9 +308,8 @@ __global__ __launch_bounds__(256) void final_kernel(FinalArgs a)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const float4 v = *reinterpret_cast<const float4 *>(rw + (int64_t)g * a.max_seq_len);
-            const double mu = st[2 * g], rs = st[2 * g + 1];
-            const float z[4] = {(float)(((double)v.x - mu) * rs), (float)(((double)v.y - mu) * rs),
-                                (float)(((double)v.z - mu) * rs), (float)(((double)v.w - mu) * rs)};
+            const ZParams zp = z_params(st[2 * g], st[2 * g + 1]);
+            const float z[4] = {z_score(v.x, zp), z_score(v.y, zp), z_score(v.z, zp), z_score(v.w, zp)};
 #pragma unroll
             for (int k = 0; k < 4; ++k) best[k] = (g == 0) ? z[k] : fmaxf(best[k], z[k]);
         }
@@ -321,7 +320,7 @@ __global__ __launch_bounds__(256) void final_kernel(FinalArgs a)
             float b = 0.f;
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                float z = (float)(((double)rw[(int64_t)g * a.max_seq_len + k] - st[2 * g]) * st[2 * g + 1]);
+                float z = z_score(rw[(int64_t)g * a.max_seq_len + k], z_params(st[2 * g], st[2 * g + 1]));
                 b = (g == 0) ? z : fmaxf(b, z);
             }
             a.final_[(int64_t)inst * a.max_seq_len + n + k] = b;

@@ -72,13 +72,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
     const float *rw = G > 0 ? a.raw + (int64_t)inst * (G > 0 ? G : 1) * a.max_seq_len : nullptr;
     uint32_t *gk = (G > 0 && !in_lds) ? a.scratch + (int64_t)inst * a.max_seq_len : nullptr;
 
-    double mu[G > 0 ? G : 1], rs[G > 0 ? G : 1];
+    ZParams zp[G > 0 ? G : 1];
     if constexpr (G > 0) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            mu[g] = a.stats[((int64_t)inst * G + g) * 2];
-            rs[g] = a.stats[((int64_t)inst * G + g) * 2 + 1];
-        }
+        for (int g = 0; g < G; ++g)
+            zp[g] = z_params(a.stats[((int64_t)inst * G + g) * 2], a.stats[((int64_t)inst * G + g) * 2 + 1]);
     }
     // key of slot n from its source (first touch)
     auto make_key = [&](int n) {
@@ -86,7 +84,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
         if constexpr (G > 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float z = (float)(((double)rw[(int64_t)g * a.max_seq_len + n] - mu[g]) * rs[g]);
+                const float z = z_score(rw[(int64_t)g * a.max_seq_len + n], zp[g]);
                 f = g == 0 ? z : fmaxf(f, z);
             }
         } else {
@@ -245,13 +243,11 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
     {
         const float *rw = G > 0 ? a.raw + (int64_t)inst * (G > 0 ? G : 1) * a.max_seq_len : nullptr;
         const float *fs = G == 0 ? a.final_ + (int64_t)inst * a.max_seq_len : nullptr;
-        double mu[G > 0 ? G : 1], rs[G > 0 ? G : 1];
+        ZParams zp[G > 0 ? G : 1];
         if constexpr (G > 0) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                mu[g] = a.stats[((int64_t)inst * G + g) * 2];
-                rs[g] = a.stats[((int64_t)inst * G + g) * 2 + 1];
-            }
+            for (int g = 0; g < G; ++g)
+                zp[g] = z_params(a.stats[((int64_t)inst * G + g) * 2], a.stats[((int64_t)inst * G + g) * 2 + 1]);
         }
 #pragma unroll
         for (int j = 0; j < KPT; ++j) {
@@ -262,7 +258,7 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
                 if constexpr (G > 0) {
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
-                        const float z = (float)(((double)rw[(int64_t)g * a.max_seq_len + n] - mu[g]) * rs[g]);
+                        const float z = z_score(rw[(int64_t)g * a.max_seq_len + n], zp[g]);
                         f = g == 0 ? z : fmaxf(f, z);
                     }
                 } else {

@@ -216,3 +216,24 @@ def test_sequence_lengths_outside_the_host_bound_are_clamped():
     for a, b in zip(*outs):
         assert torch.equal(a, b)
     assert outs[0][2].tolist() == [100, 0]
+
+
+def test_fused_step_agrees_with_the_three_calls():
+    """tri_compress_step forms the final scores inside the selection; tri_score writes them out for tri_select_topk.
+    Both go through the same z-score arithmetic, so the kept sets are identical, not merely within the tie band."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=2, n_seqs=3, n_q_heads=8, n_kv_heads=2, seq_len=5000,
+                        min_seq_len=900, budget=333, n_calib=128)
+    w = recipe.generate(cfg)
+    run = H.GpuRun(cfg, w)
+    run.build_centers()
+    run.score()
+    idx_a, cnt_a = run.select()
+    run.kept_idx.fill_(-1)
+    run.kept_cnt.fill_(-1)
+    kd, vd, pd = torch.zeros_like(run.k), torch.zeros_like(run.v), torch.zeros_like(run.pos)
+    dst = run.B.Cache(kd, vd, pd, run.seq_len, run.cur_pos, run.nmax)
+    run.B.tri_compress_step(run.model, run.centers, run.cache, dst, cfg.budget, run.kept_idx, run.kept_cnt,
+                            run.new_len, run.ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.kept_cnt.cpu().numpy(), cnt_a)
+    np.testing.assert_array_equal(run.kept_idx.cpu().numpy(), idx_a)
