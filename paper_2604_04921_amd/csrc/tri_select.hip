@@ -1,11 +1,13 @@
-// Top-B selection per head-instance (Section 4.3): exact radix select on an order-preserving
-// integer image of the float score, then an ordered emit so that the kept slots come out
-// ascending and equal scores at the threshold go to the lower slots.
+// Top-B selection per head-instance (Section 4.3): an exact select on an order-preserving integer
+// image of the float score, then an ordered emit so that the kept slots come out ascending and equal
+// scores at the threshold go to the lower slots.
 //
-// The kernel either takes final scores (tri_select_topk) or takes the raw per-head scores and the
+// Either kernel takes final scores (tri_select_topk) or takes the raw per-head scores and the
 // per-head mean / 1/sigma and forms S_final = max_g (S~(g) - mu_g) / sigma_g itself (fused step:
-// the final scores then never travel through memory).  The integer keys of a head-instance are
-// kept in LDS when they fit (32768 keys = 128 KB); longer sequences re-read them from memory.
+// the final scores then never travel through memory).  Sequences of up to 32768 keys keep their
+// integer keys in registers (select_reg_kernel: one histogram over linear score bins, exact ranking of
+// the threshold bin); longer ones use select_kernel (three radix passes over keys held in LDS or,
+// beyond 32768 keys, in a workspace area).
 #include "tri_internal.h"
 
 namespace tri {
@@ -187,8 +189,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
     }
 }
 
-// Register-resident variant for sequences of at most 1024 * KPT keys: every thread keeps KPT keys
-// (slot n = j * 1024 + tid) in registers.
+// Register-resident variant for sequences of at most THREADS * KPT keys: every thread keeps KPT keys
+// (slot n = j * THREADS + tid) in registers.  Built as 256 x 16 (up to 4096 keys: small workgroups, cheap
+// barriers, eight per CU), 1024 x 8 and 1024 x 32.
 //   1. One histogram pass over 2048 *linear* bins of the score on [-4, 12) (monotone in the score, so
 //      a valid coarse partition; z-scores spread over hundreds of bins, whereas the top bits of their
 //      float image share a handful of values and would serialise the LDS atomics).
