@@ -168,7 +168,7 @@ def main():
            "data": "synthetic",
            "config": {"workload": cfg.name, "positions": mode, "layers": L, "seqs": S, "kv_heads": Hkv,
                       "q_heads": Hq, "head_dim": d, "keys_per_seq": cfg.seq_len, "budget": B,
-                      "n_offsets": cfg.n_offsets, "storage": cfg.dtype, "layout": "paged16" if paged else "contiguous",
+                      "n_offsets": len(cfg.offsets), "storage": cfg.dtype, "layout": "paged16" if paged else "contiguous",
                       "keys": keys, "entry": "split" if args.split else "tri_compress_step",
                       "compaction": "fill" if args.fill else "ordered",
                       "keys_stored": "post-rope" if args.post_rope else "pre-rope", "score_variant": args.variant, "pairs": "half-split" if args.half_split else "interleaved",

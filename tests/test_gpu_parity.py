@@ -237,3 +237,16 @@ def test_fused_step_agrees_with_the_three_calls():
     torch.cuda.synchronize()
     np.testing.assert_array_equal(run.kept_cnt.cpu().numpy(), cnt_a)
     np.testing.assert_array_equal(run.kept_idx.cpu().numpy(), idx_a)
+
+
+@pytest.mark.parametrize("kind", ["linear17", "geometric13", "single", "sixty_four"])
+def test_offset_sets(oracle, kind):
+    """Offset sets other than the sixteen powers of two: the linear spacing and the shorter geometric range of the
+    offset ablation (Appendix G), a single offset, and the largest set the library takes (64 offsets)."""
+    sets = {"linear17": tuple(int(x) for x in np.linspace(1, 65536, 17)),
+            "geometric13": tuple(1 << j for j in range(13)),
+            "single": (4096,),
+            "sixty_four": tuple(3 * j + 1 for j in range(64))}
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=2, n_q_heads=8, n_kv_heads=2, seq_len=600,
+                        min_seq_len=250, budget=90, n_calib=128, offset_list=sets[kind])
+    run_and_check(oracle, cfg)

@@ -44,6 +44,7 @@ class Config:
     min_seq_len: Optional[int] = None   # ragged: lengths uniform in [min_seq_len, seq_len]
     block_size: int = 0                 # 0 contiguous, 16 paged
     seed: int = SEED_BASE
+    offset_list: Optional[tuple] = None # an explicit offset set (e.g. linear spacing) instead of the powers of two
 
     @property
     def group(self):
@@ -55,6 +56,8 @@ class Config:
 
     @property
     def offsets(self):
+        if self.offset_list is not None:
+            return np.array(self.offset_list, dtype=np.int64)
         return np.array([1 << j for j in range(self.n_offsets)], dtype=np.int64)
 
 
