@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--config", default="c3_model")
     ap.add_argument("--positions", default=None, choices=[None, "dense", "sparse", "sparse16", "scattered"])
     ap.add_argument("--layers", type=int, default=None, help="layer slab (configurations larger than HBM)")
+    ap.add_argument("--seqs", type=int, default=None, help="number of sequences instead of the configuration's")
     ap.add_argument("--cpu-instances", type=int, default=32, help="head-instances the CPU oracle is timed on")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--split", action="store_true", help="call the three entry points instead of the fused one")
@@ -62,6 +63,8 @@ def main():
     from workload import device, recipe
 
     cfg = recipe.CONFIGS[args.config]
+    if args.seqs:
+        cfg = recipe.scaled(cfg, n_seqs=args.seqs)
     mode = args.positions or cfg.positions
     L = args.layers or cfg.n_layers
     dev = "cuda"
