@@ -241,7 +241,9 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
     if (tid < 36) sh[tid] = 0u;
     __syncthreads();
 
-    // ---- keys into registers, histogram of their linear bins
+    // ---- keys into registers, histogram of their linear bins.  A slot past the end holds key 0, which no finite
+    // score maps to (the smallest, -inf, is 0x007fffff) and which lies below every threshold: the later phases
+    // need no bounds test, only "key != 0" where a bin is recomputed.
     uint32_t key[KPT];
     {
         const float *rw = G > 0 ? a.raw + (int64_t)inst * (G > 0 ? G : 1) * a.max_seq_len : nullptr;
@@ -252,24 +254,35 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
             for (int g = 0; g < G; ++g)
                 zp[g] = z_params(a.stats[((int64_t)inst * G + g) * 2], a.stats[((int64_t)inst * G + g) * 2 + 1]);
         }
+        // Rows are taken 16 at a time (fewer with many query heads, and in the 256-thread variant, whose occupancy
+        // depends on its register count; measured: 16 rows 729 us on config 3, was 940; 8 rows 216 us at steady state,
+        // was 240): first the keys of the chunk with unconditional loads (a slot past the end
+        // re-reads the last one), so that the compiler may issue the loads of many rows before it waits for the
+        // first -- one row at a time the phase is bound by load latency --, then the chunk's histogram updates,
+        // whose branches also keep the next chunk's loads from being hoisted (registers).
+        constexpr int kChunkMax = THREADS == 256 ? (G > 4 ? 4 : 8) : G > 6 ? 4 : G > 4 ? 8 : 16;
+        constexpr int kChunk = KPT < kChunkMax ? KPT : kChunkMax;
 #pragma unroll
-        for (int j = 0; j < KPT; ++j) {
-            const int n = j * THREADS + tid;
-            key[j] = 0u;
-            if (n < N) {
+        for (int j0 = 0; j0 < KPT; j0 += kChunk) {
+#pragma unroll
+            for (int j = j0; j < j0 + kChunk; ++j) {
+                const int n = j * THREADS + tid;
+                const int nc = min(n, N - 1);
                 float f;
                 if constexpr (G > 0) {
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
-                        const float z = z_score(rw[(int64_t)g * a.max_seq_len + n], zp[g]);
+                        const float z = z_score(rw[(int64_t)g * a.max_seq_len + nc], zp[g]);
                         f = g == 0 ? z : fmaxf(f, z);
                     }
                 } else {
-                    f = fs[n];
+                    f = fs[nc];
                 }
-                key[j] = order_key(f);
-                atomicAdd(&hist[linear_bin(key[j])], 1u);
+                key[j] = n < N ? order_key(f) : 0u;
             }
+#pragma unroll
+            for (int j = j0; j < j0 + kChunk; ++j)
+                if (key[j] != 0u) atomicAdd(&hist[linear_bin(key[j])], 1u);
         }
     }
     __syncthreads();
@@ -311,7 +324,7 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
         const int n = j * THREADS + tid;
-        const bool hit = n < N && linear_bin(key[j]) == sel_bin;
+        const bool hit = key[j] != 0u && linear_bin(key[j]) == sel_bin;
         const uint64_t hm = __ballot(hit);
         if (hm) {
             uint32_t base = 0u;
@@ -358,7 +371,7 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
             uint32_t c = 0u;
 #pragma unroll
             for (int j = 0; j < KPT; ++j) {
-                const bool in = j * THREADS + tid < N && linear_bin(key[j]) == sel_bin;
+                const bool in = key[j] != 0u && linear_bin(key[j]) == sel_bin;
                 c += (uint32_t)__popcll(__ballot(in && (key[j] & mask) == prefix && (key[j] & bm) != 0u));
             }
             if (lane == 0 && c) atomicAdd(&sh[4 + bit], c);
@@ -375,8 +388,7 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
     // ---- ordered emit: slot order is row-major (row j, then wave, then lane)
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
-        const bool in = j * THREADS + tid < N;
-        const uint64_t gm = __ballot(in && key[j] > thr), em = __ballot(in && key[j] == thr);
+        const uint64_t gm = __ballot(key[j] > thr), em = __ballot(key[j] == thr);
         if (lane == 0) {
             row_g[j * kWaves + wave] = (uint32_t)__popcll(gm);
             row_e[j * kWaves + wave] = (uint32_t)__popcll(em);
@@ -415,8 +427,7 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
 #pragma unroll
     for (int j = 0; j < KPT; ++j) {
         const int n = j * THREADS + tid;
-        const bool in = n < N;
-        const bool gt = in && key[j] > thr, eq = in && key[j] == thr;
+        const bool gt = key[j] > thr, eq = key[j] == thr;
         const uint64_t gm = __ballot(gt), em = __ballot(eq);
         const uint32_t g_before = row_g[j * kWaves + wave] + (uint32_t)__popcll(gm & below);
         const uint32_t e_before = row_e[j * kWaves + wave] + (uint32_t)__popcll(em & below);
