@@ -108,9 +108,9 @@ tri_status check_cache(const tri_model *m, const tri_cache *c, bool need_v, cons
     }
     const int eb = c->dtype == TRI_BF16 ? 2 : 4;
     const int64_t a16 = 16 / eb;
-    if (c->stride_slot < kHeadDim || c->stride_slot % a16 || c->stride_head % a16 || c->stride_layer % a16 ||
+    if (c->stride_slot < kHeadDim || c->stride_slot > 0x7fffffff || c->stride_slot % a16 || c->stride_head % a16 || c->stride_layer % a16 ||
         c->stride_seq_or_block % a16 || ((uintptr_t)c->k & 15) || ((uintptr_t)c->v & 15)) {
-        set_error("%s cache: slots must be 16-byte aligned and at least head_dim elements apart", what);
+        set_error("%s cache: slots must be 16-byte aligned, at least head_dim and less than 2^31 elements apart", what);
         return TRI_ERR_INVALID_ARG;
     }
     if (c->stride_head < 0 || c->stride_layer < 0 || c->stride_seq_or_block < 0 || c->pos_stride_head < 0 ||

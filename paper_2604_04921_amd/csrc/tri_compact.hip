@@ -57,16 +57,21 @@ __device__ __forceinline__ uint4 load_stream16(const char *p)
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-// dst and src are different memory: a plain gather.  grid (ceil(B/8), instances), block 128.
+// dst and src are different memory: a plain gather.  grid (ceil(B / rows per block), instances), block 128: the
+// row block is the fastest grid index, so workgroups that run together write neighbouring rows.
+// The workgroups are so small (one 16-byte piece of one row per thread) that their fixed cost matters -- the
+// kernel is bound by instruction issue, much of it integer division and 64-bit index arithmetic: two
+// divisions decode the instance, row16 is a power of two, and everything uniform stays in scalar registers.
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(CompactArgs a)
 {
     const int inst = blockIdx.y;
-    int l, s, h;
-    decode_inst(a.src, inst, l, s, h);
+    const int ls = inst / a.src.n_kv_heads, h = inst - ls * a.src.n_kv_heads;
+    const int l = ls / a.src.n_seqs, s = ls - l * a.src.n_seqs;
     const int cnt = read_cnt(a, inst);
     if (blockIdx.x == 0) write_new_len(a, l, s, h, cnt);
-    const int rows_per_pass = kGatherThreads / a.row16;
-    const int r = threadIdx.x / a.row16, part = threadIdx.x % a.row16;
+    const int row_shift = a.row16 == 16 ? 4 : 5;   // bf16 rows are 16 pieces of 16 bytes, fp32 rows 32
+    const int rows_per_pass = kGatherThreads >> row_shift;
+    const int r = threadIdx.x >> row_shift, part = threadIdx.x & (a.row16 - 1);
     const int32_t *idx = a.kept_idx + (int64_t)inst * a.budget;
     const char *sk = (const char *)a.src.k, *sv = (const char *)a.src.v;
     char *dk = (char *)a.dst.k, *dv = (char *)a.dst.v;

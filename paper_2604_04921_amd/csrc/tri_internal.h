@@ -54,12 +54,18 @@ __device__ __forceinline__ ZParams z_params(double mu, double inv_sigma)
 __device__ __forceinline__ float z_score(float raw, const ZParams &p) { return ((raw - p.mu_hi) - p.mu_lo) * p.rs; }
 
 // Element offset of slot n of (layer, seq, head) in k / v.
+// The slot stride is below 2^31 (checked on the host) and n >= 0, so the per-lane product is one 32 x 32 -> 64
+// bit multiply; everything else is uniform over a workgroup and stays in scalar registers.
+__device__ __forceinline__ int64_t slot_offset(const CacheView &c, int n)
+{
+    return (int64_t)((uint64_t)(uint32_t)n * (uint32_t)c.stride_slot);
+}
 __device__ __forceinline__ int64_t kv_offset(const CacheView &c, int l, int s, int h, int n)
 {
     int64_t base = (int64_t)l * c.stride_layer + (int64_t)h * c.stride_head;
-    if (c.block_shift < 0) return base + (int64_t)s * c.stride_sb + (int64_t)n * c.stride_slot;
+    if (c.block_shift < 0) return base + (int64_t)s * c.stride_sb + slot_offset(c, n);
     int b = c.block_table[(int64_t)s * c.max_blocks + (n >> c.block_shift)];
-    return base + (int64_t)b * c.stride_sb + (int64_t)(n & ((1 << c.block_shift) - 1)) * c.stride_slot;
+    return base + (int64_t)b * c.stride_sb + slot_offset(c, n & ((1 << c.block_shift) - 1));
 }
 
 // Element offset of slot n of (layer, seq, head) in pos.
