@@ -342,12 +342,8 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     auto process_group = [&](int n, const uint4(&kraw)[4], int praw, auto full_tag) {
         constexpr bool kFull = decltype(full_tag)::value;   // all 16 keys of the group exist
         uint4 kd[4];
-        int pp[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            kd[t] = to_consumer(kraw[t]);
-            pp[t] = ROTATED ? 0 : __builtin_amdgcn_ds_bpermute(perm_p + 16 * t, praw);
-        }
+        for (int t = 0; t < 4; ++t) kd[t] = to_consumer(kraw[t]);
         float kept[NG];
 #pragma unroll
         for (int q = 0; q < NG; ++q) kept[q] = 0.f;
@@ -361,26 +357,32 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
                 for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
             }
         } else {
-            // common case: all 16 positions of the group fall in the table around the current base
-            const unsigned far = max(max((unsigned)(pp[0] - base), (unsigned)(pp[1] - base)),
-                                     max((unsigned)(pp[2] - base), (unsigned)(pp[3] - base)));
-            bool fast = __builtin_amdgcn_ballot_w64(far >= (unsigned)kPhasorRange) == 0ull;
+            // common case: all 16 positions of the group fall in the table around the current base.  The test
+            // and the table index are formed on the positions in load order (every lane holds one of the 16),
+            // before they go to the consumer lanes.
+            int rraw = praw - base;
+            bool fast = __builtin_amdgcn_ballot_w64((unsigned)rraw >= (unsigned)kPhasorRange) == 0ull;
             if (!fast) {
-                // span of the 16 positions (lanes 0..3 hold four each)
-                int lo = min(min(pp[0], pp[1]), min(pp[2], pp[3])), hi = max(max(pp[0], pp[1]), max(pp[2], pp[3]));
-                lo = min(min(__builtin_amdgcn_readlane(lo, 0), __builtin_amdgcn_readlane(lo, 1)),
-                         min(__builtin_amdgcn_readlane(lo, 2), __builtin_amdgcn_readlane(lo, 3)));
-                hi = max(max(__builtin_amdgcn_readlane(hi, 0), __builtin_amdgcn_readlane(hi, 1)),
-                         max(__builtin_amdgcn_readlane(hi, 2), __builtin_amdgcn_readlane(hi, 3)));
+                // span of the 16 positions: lanes 0..15 hold one each (one DPP row)
+                int lo = praw, hi = praw;
+#pragma unroll
+                for (int o = 8; o >= 1; o >>= 1) {
+                    lo = min(lo, __shfl_xor(lo, o, 16));
+                    hi = max(hi, __shfl_xor(hi, o, 16));
+                }
+                lo = __builtin_amdgcn_readfirstlane(lo);
+                hi = __builtin_amdgcn_readfirstlane(hi);
                 if ((int64_t)hi - (int64_t)lo < kPhasorRange) {
                     move_base(lo);
+                    rraw = praw - base;
                     fast = true;
                 }
             }
             if (fast) {
                 float out[4][NG];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) step_table(kd[t], pp[t] - base, out[t]);
+                for (int t = 0; t < 4; ++t)
+                    step_table(kd[t], __builtin_amdgcn_ds_bpermute(perm_p + 16 * t, rraw), out[t]);
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -389,7 +391,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     float out[NG];
-                    step_general(kd[t], pp[t], out);
+                    step_general(kd[t], __builtin_amdgcn_ds_bpermute(perm_p + 16 * t, praw), out);
 #pragma unroll
                     for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
                 }
