@@ -355,7 +355,7 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
     // MFMA kernel: bf16, a group of 16 slots never straddling a block, 32-bit row offsets
     const bool fast = c.dtype == TRI_BF16 && (c.block_size == 0 || c.block_size >= 16) &&
-                      c.stride_slot * 2 * 16 < ((int64_t)1 << 31);
+                      c.stride_slot * 2 * 16 < ((int64_t)1 << 31) && ((int64_t)G * c.max_seq_len + 16) * 4 < ((int64_t)1 << 32);
     const int tile_keys = fast ? kFastChunk : kScoreTile;
     sa.n_tiles = (c.max_seq_len + tile_keys - 1) / tile_keys;
     tri_status rc = TRI_OK;

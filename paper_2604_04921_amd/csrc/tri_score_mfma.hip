@@ -188,6 +188,12 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     int base = 0;                      // base = 0 with the unrotated table is a valid state
     const int sub = (lane >> 2) & 3;   // which of 4 consecutive steps this lane keeps for the store
     const int row = lane >> 4;         // key of the step this lane holds after the reduction
+    // byte offset of the lane's raw score inside its group's rows: head 4q + i, key 4*sub + row (below 2^32: checked
+    // on the host)
+    uint32_t st_off[NG];
+#pragma unroll
+    for (int q = 0; q < NG; ++q)
+        st_off[q] = ((uint32_t)(4 * q + i) * (uint32_t)c.max_seq_len + (uint32_t)(4 * sub + row)) * 4u;
 
     // Addresses.  Everything that depends on the group is wave-uniform (scalar registers); a lane
     // adds its own constant offset: key (4t + i) of the group, 16-byte piece b of the row.
@@ -239,7 +245,12 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
         const int32_t *pq;
         group_ptrs(n, kp, pq);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) kd[t] = load_stream16(kp + koff[t]);
+        for (int t = 0; t < 4; ++t) {
+            // the offset stays an opaque 32-bit register here: widened once outside the loop it would turn every
+            // load address into a 64-bit vector add instead of (scalar base + 32-bit vector offset)
+            asm volatile("" : "+v"(koff[t]));
+            kd[t] = load_stream16(kp + koff[t]);
+        }
         pp = ROTATED ? 0 : pq[ld_piece];
     };
 
@@ -399,12 +410,14 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
         }
         // lane (row, sub, j) now holds key n + 4*sub + row for head j (+4q): 16 keys x 4 heads per wave
         const int key = n + 4 * sub + row;
+        char *rw_group = reinterpret_cast<char *>(rw + n);   // uniform; the lane adds its constant 32-bit offset
         if (kFull || key < w1) {
 #pragma unroll
             for (int q = 0; q < NG; ++q) {
                 const int g = 4 * q + i;
                 if (g < G) {
-                    rw[(int64_t)g * c.max_seq_len + key] = kept[q];
+                    asm volatile("" : "+v"(st_off[q]));   // keeps (scalar base + 32-bit vector offset), as for the loads
+                    *reinterpret_cast<float *>(rw_group + st_off[q]) = kept[q];
                     const double v = (double)kept[q];
                     s1[q] += v;
                     s2[q] += v * v;
