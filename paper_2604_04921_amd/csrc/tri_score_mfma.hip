@@ -212,6 +212,7 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     uint32_t koff[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) koff[t] = (uint32_t)(4 * t + ld_key) * slot_bytes + (uint32_t)ld_piece * 16u;
+    uint32_t pos_off = (uint32_t)ld_piece * 4u;   // the lane's position inside a group's 16 (same addressing trick)
     const int perm_k = (16 * i + b) * 4;   // ds_bpermute address: source lane of this lane's K piece
     const int perm_p = i * 4;              // source lane (4t + i) of this lane's position at step t, plus 16*t
 
@@ -251,7 +252,12 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
             asm volatile("" : "+v"(koff[t]));
             kd[t] = load_stream16(kp + koff[t]);
         }
-        pp = ROTATED ? 0 : pq[ld_piece];
+        if constexpr (ROTATED) {
+            pp = 0;
+        } else {
+            asm volatile("" : "+v"(pos_off));
+            pp = *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(pq) + pos_off);
+        }
     };
 
     // last, partial group: keys past the end repeat the last one (their results are discarded)
