@@ -7,7 +7,9 @@
 // (columns = query heads j).  Per band the lane produces the rotated key (Re, Im) and the modulus
 // and feeds each as an A operand; the B operand is the lane's own table entry (band, component,
 // head j = lane % 4), held in registers.  Twelve MFMAs accumulate the lane's four bands; the sixteen
-// blocks are then summed with two lane swaps and two row rotations.
+// blocks are then summed with two lane swaps per step and two row rotations shared by the four steps of a
+// group (each halving keeps only the lanes whose result survives, so the group's 16 keys x 4 heads end up
+// in one register, one value per lane, ready for a single coalesced store).
 //
 // Rotation of the key (Sections 4.1-4.2, Appendix B.2): k e^{i w p} = (k e^{i w r}) e^{i w base}
 // with r = p - base in [0, R).  e^{i w r} comes from a table in LDS (one 16-byte read per two
@@ -57,8 +59,8 @@ __device__ __forceinline__ float row_ror_add(float c, int ctrl_is_8)
 }
 
 // Sum the 16 blocks of a 4x4x1 accumulator.  In: lane (b, j) reg i = partial of (key i, head j) over
-// the lane's 4 bands.  Out: every lane of row r (lanes 16r..16r+15) with lane % 4 = j holds the
-// total of (key r, head j).
+// the lane's 4 bands.  Out: lane q of row r (lanes 16r..16r+15) holds the sum over blocks q/4, q/4+4, q/4+8,
+// q/4+12 of (key r, head q % 4); merge_steps() adds the four lanes of a row that share a head.
 __device__ __forceinline__ float reduce_blocks(float4v acc)
 {
     auto s02 = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[0]), __float_as_uint(acc[2]), false, false);
@@ -67,10 +69,27 @@ __device__ __forceinline__ float reduce_blocks(float4v acc)
     const float a0 = __uint_as_float(s02[0]) + __uint_as_float(s02[1]);
     const float a1 = __uint_as_float(s13[0]) + __uint_as_float(s13[1]);
     auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(a0), __float_as_uint(a1), false, false);
-    float c = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);   // row r now holds key r
-    c = row_ror_add(c, 1);
-    c = row_ror_add(c, 0);
-    return c;
+    return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);   // row r now holds key r, still split over its 4 blocks
+}
+
+// Finishes the block sums of four steps at once.  In: c0..c3 = reduce_blocks() of four steps (lane q of a
+// row = block q / 4 of that row, head q % 4).  Out: lane q holds the total of step q / 4, head q % 4 -- the
+// last two halvings write only the lanes that keep their result (DPP bank mask), so the four steps end up
+// side by side in one register without a select.
+__device__ __forceinline__ float merge_steps(float c0, float c1, float c2, float c3)
+{
+    // blocks (q/4, q/4 ^ 2): lanes 0-7 of a row take the first step of the pair, lanes 8-15 the second
+    float m01 = row_ror_add(c3, 1), m23 = row_ror_add(c2, 1);
+    // a VALU result needs two wait states before a DPP read; the compiler does not see into the statement
+    asm("s_nop 1\n\tv_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0x3" : "+v"(m01) : "v"(c1));
+    asm("s_nop 1\n\tv_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0x3" : "+v"(m23) : "v"(c0));
+    // m01 = (step 1 | step 3), m23 = (step 0 | step 2), each still split over blocks (q/4, q/4 ^ 1).
+    // lanes 4-7 and 12-15 of m01 + (m01 from 4 lanes below) are the totals of steps 1 and 3 ...
+    const int v = __float_as_int(m01);
+    float f = m01 + __int_as_float(__builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true));
+    // ... and lanes 0-3 and 8-11 of m23 + (m23 from 4 lanes above) those of steps 0 and 2
+    asm("s_nop 1\n\tv_add_f32_dpp %0, %1, %1 row_shl:4 row_mask:0xf bank_mask:0x5" : "+v"(f) : "v"(m23));
+    return f;
 }
 
 // The lane's slice of the folded centre table for one group of four query heads, rotated by
@@ -361,18 +380,11 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
         uint4 kd[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) kd[t] = to_consumer(kraw[t]);
-        float kept[NG];
-#pragma unroll
-        for (int q = 0; q < NG; ++q) kept[q] = 0.f;
+        float out[4][NG];   // per step, block sums not yet finished (reduce_blocks)
         if constexpr (ROTATED) {   // post-RoPE keys: straight into the contraction
             const float one[4] = {1.f, 1.f, 1.f, 1.f}, zero[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                float out[NG];
-                score_step<NG, false, HALF>(kd[t], one, zero, tb, out);
-#pragma unroll
-                for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
-            }
+            for (int t = 0; t < 4; ++t) score_step<NG, false, HALF>(kd[t], one, zero, tb, out[t]);
         } else {
             // common case: all 16 positions of the group fall in the table around the current base.  The test
             // and the table index are formed on the positions in load order (every lane holds one of the 16),
@@ -396,24 +408,18 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
                 }
             }
             if (fast) {
-                float out[4][NG];
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
                     step_table(kd[t], __builtin_amdgcn_ds_bpermute(perm_p + 16 * t, rraw), out[t]);
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[t][q] : kept[q];
             } else {
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    float out[NG];
-                    step_general(kd[t], __builtin_amdgcn_ds_bpermute(perm_p + 16 * t, praw), out);
-#pragma unroll
-                    for (int q = 0; q < NG; ++q) kept[q] = (sub == t) ? out[q] : kept[q];
-                }
+                for (int t = 0; t < 4; ++t)
+                    step_general(kd[t], __builtin_amdgcn_ds_bpermute(perm_p + 16 * t, praw), out[t]);
             }
         }
+        float kept[NG];   // the lane's own result: step sub
+#pragma unroll
+        for (int q = 0; q < NG; ++q) kept[q] = merge_steps(out[0][q], out[1][q], out[2][q], out[3][q]);
         // lane (row, sub, j) now holds key n + 4*sub + row for head j (+4q): 16 keys x 4 heads per wave
         const int key = n + 4 * sub + row;
         char *rw_group = reinterpret_cast<char *>(rw + n);   // uniform; the lane adds its constant 32-bit offset
