@@ -3,6 +3,7 @@
 #include <cstdio>
 
 #include "tri_internal.h"
+#include "tri_score_common.h"
 
 namespace tri {
 
@@ -168,6 +169,8 @@ Workspace workspace_layout(const tri_model &m, const tri_cache &c, int32_t budge
     o = align256(o + 128 * 1024);
     w.table = o;
     o = align256(o + inst * kBands * 3 * G * sizeof(float));
+    w.work = o;
+    o = align256(o + fast_work_ints(c.n_seqs, c.max_seq_len) * sizeof(int32_t));
     w.partials = o;
     o = align256(o + inst * tiles * 2 * G * sizeof(double));
     w.stats = o;

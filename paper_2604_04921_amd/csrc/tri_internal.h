@@ -83,6 +83,7 @@ struct Workspace {
     size_t fold_phasors;   // double [1 + S][F][2]: mean over the offsets of e^{i w delta}; e^{i w cur_pos[s]}
     size_t phasors;    // relative-position phasor table of the MFMA score kernel
     size_t table;      // float  [L][S][Hkv][F][3][G]: folded centre table
+    size_t work;       // int32: item counter and work list of the MFMA score kernel
     size_t partials;   // double [L][S][Hkv][n_tiles][2G]: per-tile sum and sum of squares
     size_t stats;      // double [L][S][Hkv][G][2]: mean and 1/sigma
     size_t raw;        // float  [L][S][Hq][Nmax] (used when the caller passes no raw_out)

@@ -364,7 +364,7 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
     const bool timed = timing_next(&ev0, &ev1);
     if (timed) (void)hipEventRecord(ev0, st);
     if (fast) {
-        rc = launch_score_fast(G, sa, m.n_layers, m.pairs == TRI_PAIR_HALF, st);
+        rc = launch_score_fast(G, sa, m.pairs == TRI_PAIR_HALF, st);
     } else {
         dim3 grid(sa.n_tiles, c.n_seqs * m.n_kv_heads, m.n_layers);
         rc = (c.dtype == TRI_BF16) ? launch_score_kernel<G, uint16_t>(m, sa, grid, st)
@@ -419,6 +419,8 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     sa.raw = raw_out ? raw_out : reinterpret_cast<float *>(ws + wl.raw);
     sa.partials = reinterpret_cast<double *>(ws + wl.partials);
     sa.phasors = reinterpret_cast<const uint4 *>(ws + wl.phasors);
+    sa.work = reinterpret_cast<int32_t *>(ws + wl.work);
+    sa.n_layers = m.n_layers;
     FinalArgs fa{sa.raw, reinterpret_cast<double *>(ws + wl.stats), final_out, c.seq_len, c.n_seqs,
                  m.n_kv_heads, c.max_seq_len};
     switch (G) {

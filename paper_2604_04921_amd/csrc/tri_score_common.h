@@ -12,6 +12,8 @@ struct ScoreArgs {
     float *raw;              // [L][S][Hq][Nmax]
     double *partials;        // [L][S][Hkv][n_tiles][2G]: per-tile sum and sum of squares
     int32_t n_tiles;         // tiles per head-instance in `partials`
+    int32_t n_layers;
+    int32_t *work;           // MFMA kernel only: item counter and work list (kFastWorkInts(S, Nmax) ints)
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -27,6 +29,11 @@ constexpr int kPhasorBytes = 2 * kPhasorHalfStride;
 
 tri_status launch_phasor_table(double theta, uint4 *phasors, hipStream_t st);
 // bf16 keys; G in 1..8
-tri_status launch_score_fast(int G, const ScoreArgs &sa, int n_layers, bool half_split, hipStream_t st);
+tri_status launch_score_fast(int G, const ScoreArgs &sa, bool half_split, hipStream_t st);
+// ints the MFMA kernel's work list takes: a header and one (sequence, chunk) pair per possible chunk
+inline size_t fast_work_ints(int64_t n_seqs, int64_t max_seq_len)
+{
+    return 4 + 2 * (size_t)n_seqs * (size_t)((max_seq_len + kFastChunk - 1) / kFastChunk);
+}
 
 }  // namespace tri

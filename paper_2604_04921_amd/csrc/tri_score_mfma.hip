@@ -16,6 +16,7 @@
 // bands); e^{-i w base} is folded into the lane's table registers whenever the wave moves its base.
 // A step whose four keys span R positions or more takes the direct path instead (phase in double,
 // v_sin_f32 / v_cos_f32), so any position layout is handled.
+#include <algorithm>
 #include <type_traits>
 
 #include "tri_score_common.h"
@@ -148,9 +149,45 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
     for (int q = 0; q < NG; ++q) out[q] = reduce_blocks(acc[q]);
 }
 
-// grid (ceil(Nmax / kFastChunk), S*Hkv, L), block 512.  The workgroup's keys (8192, fewer in the last
-// chunk of a sequence) are split evenly over its 8 waves; each wave walks its contiguous share in
-// groups of 16 (4 steps).  PAGED: block_size >= 16, so a group never straddles a block.
+// One entry of the work list per (sequence, chunk of kFastChunk keys) that exists, written by work_list_kernel
+// from the sequence lengths on the device: [0] next item (the kernel's shared counter), [1] entries per
+// (layer, KV head), then (sequence, chunk) pairs.
+constexpr int kWorkHeader = 4;
+
+// grid 1, block 256
+__global__ __launch_bounds__(256) void work_list_kernel(const int32_t *seq_len, int n_seqs, int max_seq_len, int32_t *work)
+{
+    __shared__ int start[257];
+    const int tid = threadIdx.x;
+    const int seg = (n_seqs + 255) / 256, s0 = min(n_seqs, tid * seg), s1 = min(n_seqs, s0 + seg);
+    int cnt = 0;
+    for (int s = s0; s < s1; ++s) cnt += (clamp_len(seq_len[s], max_seq_len) + kFastChunk - 1) / kFastChunk;
+    start[tid + 1] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+        start[0] = 0;
+        for (int k = 1; k <= 256; ++k) start[k] += start[k - 1];
+        work[0] = 0;
+        work[1] = start[256];
+    }
+    __syncthreads();
+    int o = start[tid];
+    for (int s = s0; s < s1; ++s) {
+        const int n = (clamp_len(seq_len[s], max_seq_len) + kFastChunk - 1) / kFastChunk;
+        for (int ch = 0; ch < n; ++ch, ++o) {
+            work[kWorkHeader + 2 * o] = s;
+            work[kWorkHeader + 2 * o + 1] = ch;
+        }
+    }
+}
+
+// grid = as many workgroups as the GPU holds at once, block 512.  A workgroup stays for the whole launch and
+// takes items -- one (layer, KV head, sequence, chunk of 8192 keys) each -- from a shared counter until they run
+// out; the phasor table is loaded once per workgroup, and neither empty chunks of short sequences nor the order
+// in which the hardware hands workgroups to the XCDs cost anything (with one workgroup per chunk slot of the
+// longest sequence, ragged batches lost up to a quarter of the kernel's throughput to the empty ones).  The item's
+// keys are split evenly over the 8 waves; each wave walks its contiguous share in groups of 16 (4 steps).
+// PAGED: block_size >= 16, so a group never straddles a block.
 template <int G, bool PAGED, bool ROTATED, bool HALF>
 __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
 {
@@ -159,25 +196,36 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
     __shared__ double red[kFastWaves][2 * 4 * NG];
     __shared__ double lds_rev[kBands];          // omega_f / 2pi
     __shared__ float lds_tab[kBands * 3 * G];   // this head-instance's folded table (no base)
+    __shared__ int lds_item;
 
     const CacheView &c = a.c;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps loop control scalar
     const int b = lane >> 2, i = lane & 3;
-    // Workgroups go to the 8 XCDs round-robin by linear index, so with gridDim.x a multiple of 8 chunk c of
-    // every head-instance would land on XCD c -- and with ragged sequence lengths the XCDs that own the high
-    // chunks would idle.  Rotating the chunk index by the instance index spreads every chunk over all XCDs.
-    const int chunk = (blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x;
-    const int s = blockIdx.y / c.n_kv_heads, h = blockIdx.y % c.n_kv_heads;
-    const int l = blockIdx.z;
-    const int N = clamp_len(c.seq_len[s], c.max_seq_len);
-    if (chunk * kFastChunk >= N) return;   // uniform over the workgroup
 
-    const int64_t inst = ((int64_t)l * c.n_seqs + s) * c.n_kv_heads + h;
     if constexpr (!ROTATED)
         for (int k = tid; k < kPhasorBytes / 16; k += kFastThreads) lds_phasors[k] = a.phasors[k];
-    for (int k = tid; k < kBands * 3 * G; k += kFastThreads) lds_tab[k] = a.table[inst * (kBands * 3 * G) + k];
     if (tid < kBands) lds_rev[tid] = a.band_rev[tid];
+    const int per_lh = __builtin_amdgcn_readfirstlane(a.work[1]);   // items per (layer, KV head)
+    const int n_items = per_lh * a.n_layers * c.n_kv_heads;       // below 2^31: checked on the host
+    int next_item = 0;
+    if (tid == 0) next_item = atomicAdd(&a.work[0], 1);
+
+  for (;;) {
+    // every wave has finished the previous item when it arrives here: lds_tab, red and lds_item are free
+    if (tid == 0) lds_item = next_item;
+    __syncthreads();
+    const int item = __builtin_amdgcn_readfirstlane(lds_item);
+    if (item >= n_items) break;   // uniform over the workgroup; the counter only grows, so every workgroup gets here
+    if (tid == 0) next_item = atomicAdd(&a.work[0], 1);   // in flight while this item is scored
+    const int lh = item / per_lh, wi = item - lh * per_lh;
+    const int l = lh / c.n_kv_heads, h = lh - l * c.n_kv_heads;
+    const int s = __builtin_amdgcn_readfirstlane(a.work[kWorkHeader + 2 * wi]);
+    const int chunk = __builtin_amdgcn_readfirstlane(a.work[kWorkHeader + 2 * wi + 1]);
+    const int N = clamp_len(c.seq_len[s], c.max_seq_len);   // chunk * kFastChunk < N by construction of the list
+
+    const int64_t inst = ((int64_t)l * c.n_seqs + s) * c.n_kv_heads + h;
+    for (int k = tid; k < kBands * 3 * G; k += kFastThreads) lds_tab[k] = a.table[inst * (kBands * 3 * G) + k];
     __syncthreads();
 
     LaneTable tb[NG];
@@ -484,10 +532,11 @@ __global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
         for (int w = 0; w < kFastWaves; ++w) v += red[w][g * 2 + which];
         a.partials[(inst * a.n_tiles + chunk) * (2 * G) + tid] = v;
     }
+  }   // next item
 }
 
 template <int G>
-tri_status launch_fast_g(const ScoreArgs &sa, int n_layers, bool half_split, hipStream_t st)
+tri_status launch_fast_g(const ScoreArgs &sa, bool half_split, hipStream_t st)
 {
     const bool paged = sa.c.block_shift >= 0;
     auto pick = [&](auto half) {
@@ -499,8 +548,29 @@ tri_status launch_fast_g(const ScoreArgs &sa, int n_layers, bool half_split, hip
     const int lds = sa.c.k_rotated ? 0 : kPhasorBytes;   // no phasor table for post-RoPE keys
     if (lds && hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return hip_status("hipFuncSetAttribute(score_mfma_kernel)");
-    dim3 grid(sa.n_tiles, sa.c.n_seqs * sa.c.n_kv_heads, n_layers);
-    hipLaunchKernelGGL(kern, grid, dim3(kFastThreads), lds, st, sa);
+    // as many workgroups as are resident at once (they stay until the work list is empty), no more than items can exist
+    static int resident[2][2][2];   // per kernel of this G: asked once (all GPUs of a process are the same model)
+    int &slots = resident[sa.c.k_rotated ? 1 : 0][paged ? 1 : 0][half_split ? 1 : 0];
+    if (slots == 0) {
+        int dev = 0, n_cu = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kern, kFastThreads, lds) != hipSuccess ||
+            n_cu <= 0 || per_cu <= 0) {
+            (void)hipGetLastError();
+            set_error("score: occupancy query failed");
+            return TRI_ERR_HIP;
+        }
+        slots = n_cu * per_cu;
+    }
+    const int64_t max_items = (int64_t)sa.n_tiles * sa.c.n_seqs * sa.c.n_kv_heads * sa.n_layers;
+    if (max_items > (int64_t)0x7fff0000) {   // the item counter is a 32-bit integer
+        set_error("score: %lld chunks of %d keys exceed the 32-bit work counter", (long long)max_items, kFastChunk);
+        return TRI_ERR_UNSUPPORTED;
+    }
+    const int grid = (int)std::min<int64_t>((int64_t)slots, max_items);
+    hipLaunchKernelGGL(work_list_kernel, dim3(1), dim3(256), 0, st, sa.c.seq_len, sa.c.n_seqs, sa.c.max_seq_len, sa.work);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kFastThreads), lds, st, sa);
     return hip_status("score_mfma_kernel");
 }
 
@@ -513,17 +583,17 @@ tri_status launch_phasor_table(double theta, uint4 *phasors, hipStream_t st)
     return hip_status("phasor_table_kernel");
 }
 
-tri_status launch_score_fast(int G, const ScoreArgs &sa, int n_layers, bool half_split, hipStream_t st)
+tri_status launch_score_fast(int G, const ScoreArgs &sa, bool half_split, hipStream_t st)
 {
     switch (G) {
-        case 1: return launch_fast_g<1>(sa, n_layers, half_split, st);
-        case 2: return launch_fast_g<2>(sa, n_layers, half_split, st);
-        case 3: return launch_fast_g<3>(sa, n_layers, half_split, st);
-        case 4: return launch_fast_g<4>(sa, n_layers, half_split, st);
-        case 5: return launch_fast_g<5>(sa, n_layers, half_split, st);
-        case 6: return launch_fast_g<6>(sa, n_layers, half_split, st);
-        case 7: return launch_fast_g<7>(sa, n_layers, half_split, st);
-        case 8: return launch_fast_g<8>(sa, n_layers, half_split, st);
+        case 1: return launch_fast_g<1>(sa, half_split, st);
+        case 2: return launch_fast_g<2>(sa, half_split, st);
+        case 3: return launch_fast_g<3>(sa, half_split, st);
+        case 4: return launch_fast_g<4>(sa, half_split, st);
+        case 5: return launch_fast_g<5>(sa, half_split, st);
+        case 6: return launch_fast_g<6>(sa, half_split, st);
+        case 7: return launch_fast_g<7>(sa, half_split, st);
+        case 8: return launch_fast_g<8>(sa, half_split, st);
     }
     set_error("group size %d not built (1 to 8)", G);
     return TRI_ERR_UNSUPPORTED;
