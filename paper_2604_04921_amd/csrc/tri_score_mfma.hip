@@ -26,8 +26,9 @@ namespace tri {
 namespace {
 
 constexpr double kTwoPi = 6.283185307179586476925286766559;
-constexpr int kFastThreads = 512;
-constexpr int kFastWaves = kFastThreads / 64;
+// Workgroup size of the score kernel: with more than four query heads per KV head a wave needs more than 128
+// registers, so only three waves fit a SIMD; 12-wave workgroups fill them (8-wave ones would leave one of three unused).
+constexpr int fast_threads(int G) { return G > 4 ? 768 : 512; }
 
 typedef float float4v __attribute__((ext_vector_type(4)));
 
@@ -181,17 +182,18 @@ __global__ __launch_bounds__(256) void work_list_kernel(const int32_t *seq_len, 
     }
 }
 
-// grid = as many workgroups as the GPU holds at once, block 512.  A workgroup stays for the whole launch and
+// grid = as many workgroups as the GPU holds at once, block 512 (768 for G > 4).  A workgroup stays for the whole launch and
 // takes items -- one (layer, KV head, sequence, chunk of 8192 keys) each -- from a shared counter until they run
 // out; the phasor table is loaded once per workgroup, and neither empty chunks of short sequences nor the order
 // in which the hardware hands workgroups to the XCDs cost anything (with one workgroup per chunk slot of the
 // longest sequence, ragged batches lost up to a quarter of the kernel's throughput to the empty ones).  The item's
-// keys are split evenly over the 8 waves; each wave walks its contiguous share in groups of 16 (4 steps).
+// keys are split evenly over the waves; each wave walks its contiguous share in groups of 16 (4 steps).
 // PAGED: block_size >= 16, so a group never straddles a block.
 template <int G, bool PAGED, bool ROTATED, bool HALF>
-__global__ __launch_bounds__(kFastThreads) void score_mfma_kernel(ScoreArgs a)
+__global__ __launch_bounds__(fast_threads(G)) void score_mfma_kernel(ScoreArgs a)
 {
     constexpr int NG = (G + 3) / 4;
+    constexpr int kFastThreads = fast_threads(G), kFastWaves = kFastThreads / 64;
     extern __shared__ uint4 lds_phasors[];
     __shared__ double red[kFastWaves][2 * 4 * NG];
     __shared__ double lds_rev[kBands];          // omega_f / 2pi
@@ -555,7 +557,7 @@ tri_status launch_fast_g(const ScoreArgs &sa, bool half_split, hipStream_t st)
         int dev = 0, n_cu = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kern, kFastThreads, lds) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kern, fast_threads(G), lds) != hipSuccess ||
             n_cu <= 0 || per_cu <= 0) {
             (void)hipGetLastError();
             set_error("score: occupancy query failed");
@@ -570,7 +572,7 @@ tri_status launch_fast_g(const ScoreArgs &sa, bool half_split, hipStream_t st)
     }
     const int grid = (int)std::min<int64_t>((int64_t)slots, max_items);
     hipLaunchKernelGGL(work_list_kernel, dim3(1), dim3(256), 0, st, sa.c.seq_len, sa.c.n_seqs, sa.c.max_seq_len, sa.work);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kFastThreads), lds, st, sa);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(fast_threads(G)), lds, st, sa);
     return hip_status("score_mfma_kernel");
 }
 
