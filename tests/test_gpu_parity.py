@@ -250,3 +250,41 @@ def test_offset_sets(oracle, kind):
     cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=2, n_q_heads=8, n_kv_heads=2, seq_len=600,
                         min_seq_len=250, budget=90, n_calib=128, offset_list=sets[kind])
     run_and_check(oracle, cfg)
+
+
+def test_many_short_sequences(oracle):
+    """More sequences than the work-list builder has threads (each thread then lists several sequences), lengths from
+    0 to a few groups: the score kernel's items are one per existing (sequence, chunk) pair, empty sequences have none."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=300, n_q_heads=8, n_kv_heads=2, seq_len=70,
+                        min_seq_len=0, budget=20, n_calib=128)
+    def lens(w):
+        w["seq_len"][::7] = 0
+    run_and_check(oracle, cfg, mutate=lens)
+
+
+def test_chunk_boundaries(oracle):
+    """Sequence lengths around the 8192-key chunk of the score kernel: one key short of a chunk, exactly one chunk,
+    one key more, and two chunks plus a ragged tail."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=4, n_q_heads=8, n_kv_heads=1, seq_len=16901,
+                        min_seq_len=16901, budget=500, n_calib=128)
+    def lens(w):
+        w["seq_len"][:] = np.array([8191, 8192, 8193, 16901], dtype=np.int32)
+    run_and_check(oracle, cfg, mutate=lens)
+
+
+def test_all_sequences_empty():
+    """No keys anywhere: the score kernel's work list is empty, every count is zero and nothing is written."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=2, n_seqs=3, n_q_heads=8, n_kv_heads=2, seq_len=300,
+                        min_seq_len=300, budget=50, n_calib=128)
+    w = recipe.generate(cfg)
+    w["seq_len"] = np.zeros(3, dtype=np.int32)
+    run = H.GpuRun(cfg, w)
+    run.build_centers()
+    k0 = run.k.clone()
+    run.kept_cnt.fill_(-1)
+    run.B.tri_compress_step(run.model, run.centers, run.cache, run.cache, cfg.budget, run.kept_idx, run.kept_cnt,
+                            run.new_len, run.ws)
+    torch.cuda.synchronize()
+    assert run.kept_cnt.cpu().numpy().tolist() == [[[0, 0]] * 3] * 2
+    assert run.new_len.cpu().numpy().tolist() == [0, 0, 0]
+    assert torch.equal(run.k.view(torch.int16), k0.view(torch.int16))
