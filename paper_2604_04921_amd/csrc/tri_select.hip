@@ -6,8 +6,8 @@
 // per-head mean / 1/sigma and forms S_final = max_g (S~(g) - mu_g) / sigma_g itself (fused step:
 // the final scores then never travel through memory).  Sequences of up to 32768 keys keep their
 // integer keys in registers (select_reg_kernel: one histogram over linear score bins, exact ranking of
-// the threshold bin); longer ones use select_kernel (three radix passes over keys held in LDS or,
-// beyond 32768 keys, in a workspace area).
+// the threshold bin); longer ones use select_kernel (the same steps over keys held in LDS or, beyond
+// 32768 keys, in a workspace area).
 #include "tri_internal.h"
 
 namespace tri {
@@ -16,7 +16,7 @@ namespace {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kSelBins = 2048;          // 11-bit digits: bits 31..21, 20..10, then the low 10 bits
+constexpr int kSelBins = 2048;          // linear score bins of the histogram pass
 constexpr int kSelLdsKeys = 32768;      // keys held in LDS at most
 
 // Monotone map float -> uint32 (larger float <=> larger key); -0.0 is folded onto +0.0.
@@ -37,6 +37,7 @@ struct SelectArgs {
     int32_t *kept_cnt;     // [inst]
     int32_t n_seqs, n_kv_heads, max_seq_len, budget, lds_keys;
     const int32_t *head_budgets;   // [L][Hkv] or NULL: budget of each (layer, KV head), at most `budget`
+    int32_t n_above, n_upto;       // select_kernel: this launch handles the head-instances with n_above < N <= n_upto
 };
 
 // The budget of head-instance `inst`: the common one, or the head's own (read into [0, budget]).
@@ -47,20 +48,35 @@ __device__ __forceinline__ int instance_budget(const SelectArgs &a, int inst)
     return min(max(a.head_budgets[l * a.n_kv_heads + h], 0), a.budget);
 }
 
+constexpr int kSelCand = 2048;   // keys of the threshold bin ranked in LDS
+
+__device__ __forceinline__ float key_to_float(uint32_t u)
+{
+    return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
+}
+__device__ __forceinline__ int linear_bin(uint32_t u)
+{
+    const float x = (key_to_float(u) + 4.0f) * 128.0f;   // 2048 bins over [-4, 12)
+    return (int)fminf(fmaxf(x, 0.0f), 2047.0f);
+}
+
 // grid (instances), block 1024.  G = 0: final scores given; G > 0: raw scores of G query heads given.
 template <int G>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
 {
     extern __shared__ uint32_t lds_keys[];
     __shared__ uint32_t hist[kSelBins];
+    __shared__ uint32_t cand_key[kSelCand];
+    __shared__ int32_t cand_idx[kSelCand];
     __shared__ uint32_t wave_tot[kSelWaves];
-    __shared__ uint32_t sel[2];
+    __shared__ uint32_t sh[36];   // 0: selected bin, 1: need inside it, 2: candidate count, 3: threshold key, 4..35: bit counters / tie count
     __shared__ uint32_t wg[2][kSelWaves], we[2][kSelWaves];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int inst = blockIdx.x;
     const int s = (inst / a.n_kv_heads) % a.n_seqs;
     const int N = clamp_len(a.seq_len[s], a.max_seq_len);
+    if (N <= a.n_above || N > a.n_upto) return;   // the other launch's head-instance (uniform over the workgroup)
     const int B = instance_budget(a, inst);
     int32_t *out = a.kept_idx + (int64_t)inst * a.budget;
     if (tid == 0) a.kept_cnt[inst] = N < B ? N : B;
@@ -101,30 +117,29 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
         else return order_key(fs[n]);
     };
 
-    // ---- threshold: the B-th largest key, one 11-bit digit at a time from the top
-    uint32_t prefix = 0u, mask = 0u;
-    uint32_t need = (uint32_t)B;
-#pragma unroll 1
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-        const uint32_t dmask = pass == 2 ? 1023u : 2047u;
-        for (int k = tid; k < kSelBins; k += kSelThreads) hist[k] = 0u;
-        __syncthreads();
-        if (pass == 0) {
-            for (int n = tid; n < N; n += kSelThreads) {
-                const uint32_t u = make_key(n);
-                if (in_lds) lds_keys[n] = u;
-                else if constexpr (G > 0) gk[n] = u;
-                atomicAdd(&hist[u >> 21], 1u);
-            }
-        } else {
-            for (int n = tid; n < N; n += kSelThreads) {
-                const uint32_t u = get_key(n);
-                if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & dmask], 1u);
+    // ---- keys to LDS / scratch, histogram of their linear score bins (see select_reg_kernel: the same three
+    // steps, with the keys in memory instead of registers).  Four rows of loads are issued before their updates.
+    for (int k = tid; k < kSelBins; k += kSelThreads) hist[k] = 0u;
+    if (tid < 36) sh[tid] = 0u;
+    __syncthreads();
+    for (int n0 = tid; n0 < N; n0 += 4 * kSelThreads) {
+        uint32_t u[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) u[j] = make_key(min(n0 + j * kSelThreads, N - 1));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + j * kSelThreads;
+            if (n < N) {
+                if (in_lds) lds_keys[n] = u[j];
+                else if constexpr (G > 0) gk[n] = u[j];
+                atomicAdd(&hist[linear_bin(u[j])], 1u);
             }
         }
-        __syncthreads();
-        // thread t owns bins 2047-2t and 2046-2t: running count from the top bin down
+    }
+    __syncthreads();
+
+    // ---- the bin holding the B-th largest: thread t owns bins 2047-2t and 2046-2t, running count from the top
+    {
         const uint32_t v0 = hist[kSelBins - 1 - 2 * tid], v1 = hist[kSelBins - 2 - 2 * tid];
         uint32_t cum = v0 + v1;
 #pragma unroll
@@ -135,21 +150,84 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
         if (lane == 63) wave_tot[wave] = cum;
         __syncthreads();
         for (int w = 0; w < wave; ++w) cum += wave_tot[w];
-        const uint32_t excl = cum - v0 - v1;
-        if (excl < need && need <= excl + v0) {          // exactly one thread and bin holds the B-th key
-            sel[0] = (uint32_t)(kSelBins - 1 - 2 * tid);
-            sel[1] = need - excl;
-        } else if (excl + v0 < need && need <= cum) {
-            sel[0] = (uint32_t)(kSelBins - 2 - 2 * tid);
-            sel[1] = need - excl - v0;
+        const uint32_t excl = cum - v0 - v1, want = (uint32_t)B;
+        if (excl < want && want <= excl + v0) {          // exactly one thread and bin holds the B-th key
+            sh[0] = (uint32_t)(kSelBins - 1 - 2 * tid);
+            sh[1] = want - excl;
+        } else if (excl + v0 < want && want <= cum) {
+            sh[0] = (uint32_t)(kSelBins - 2 - 2 * tid);
+            sh[1] = want - excl - v0;
+        }
+    }
+    __syncthreads();
+    const int sel_bin = (int)sh[0];
+    uint32_t need = sh[1];   // how many keys of the selected bin are kept (>= 1)
+
+    // ---- gather the selected bin's keys (any order; the ranks below do not depend on it)
+    for (int n0 = 0; n0 < N; n0 += kSelThreads) {
+        const int n = n0 + tid;
+        const uint32_t u = n < N ? get_key(n) : 0u;
+        const bool hit = n < N && linear_bin(u) == sel_bin;
+        const uint64_t hm = __ballot(hit);
+        if (hm) {
+            uint32_t base = 0u;
+            if (lane == 0) base = atomicAdd(&sh[2], (uint32_t)__popcll(hm));
+            base = __builtin_amdgcn_readfirstlane(base);
+            const uint32_t pos = base + (uint32_t)__popcll(hm & ((1ull << lane) - 1ull));
+            if (hit && pos < (uint32_t)kSelCand) {
+                cand_key[pos] = u;
+                cand_idx[pos] = n;
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t m = sh[2];
+    uint32_t thr;
+    if (m <= (uint32_t)kSelCand) {
+        // exact rank of every candidate among the candidates: key descending, slot ascending
+        for (uint32_t c = tid; c < m; c += kSelThreads) {
+            const uint32_t kc = cand_key[c];
+            const int32_t ic = cand_idx[c];
+            uint32_t rank = 0u;
+            for (uint32_t o = 0; o < m; ++o) {
+                const uint32_t ko = cand_key[o];
+                rank += (ko > kc || (ko == kc && cand_idx[o] < ic)) ? 1u : 0u;
+            }
+            if (rank == need - 1u) sh[3] = kc;   // the last kept candidate defines the threshold
         }
         __syncthreads();
-        prefix |= sel[0] << shift;
-        mask |= dmask << shift;
-        need = sel[1];
+        thr = sh[3];
+        // threshold ties kept = need - (candidates strictly above the threshold)
+        uint32_t above = 0u;
+        for (uint32_t c = tid; c < m; c += kSelThreads) above += cand_key[c] > thr ? 1u : 0u;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) above += __shfl_xor(above, o, 64);
+        if (lane == 0 && above) atomicAdd(&sh[4], above);
         __syncthreads();
+        need -= sh[4];
+    } else {
+        // too many keys in one bin (many equal scores): one bit at a time, keys of the bin only
+        uint32_t prefix = 0u, mask = 0u;
+#pragma unroll 1
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t bm = 1u << bit;
+            uint32_t c = 0u;
+            for (int n0 = 0; n0 < N; n0 += kSelThreads) {
+                const int n = n0 + tid;
+                const uint32_t u = n < N ? get_key(n) : 0u;
+                const bool in = n < N && linear_bin(u) == sel_bin;
+                c += (uint32_t)__popcll(__ballot(in && (u & mask) == prefix && (u & bm) != 0u));
+            }
+            if (lane == 0 && c) atomicAdd(&sh[4 + bit], c);
+            __syncthreads();
+            const uint32_t ones = sh[4 + bit];
+            if (ones >= need) prefix |= bm;
+            else need -= ones;
+            mask |= bm;
+        }
+        thr = prefix;
     }
-    const uint32_t thr = prefix;  // keys > thr are kept; of the keys == thr the first `need` slots
+    // keys > thr are kept; of the keys == thr the first `need` slots
 
     // ---- ordered emit
     uint32_t g_run = 0u, e_run = 0u;
@@ -200,18 +278,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
 //      of threshold ties to keep.  A bin with more keys than the LDS list holds (many equal scores)
 //      is resolved one bit at a time from the registers instead.
 //   3. Ordered emit with three barriers: per-(row, wave) counts from ballots, one scan, the stores.
-constexpr int kSelCand = 2048;   // keys of the threshold bin ranked in LDS
-
-__device__ __forceinline__ float key_to_float(uint32_t u)
-{
-    return __uint_as_float((u & 0x80000000u) ? (u & 0x7fffffffu) : ~u);
-}
-__device__ __forceinline__ int linear_bin(uint32_t u)
-{
-    const float x = (key_to_float(u) + 4.0f) * 128.0f;   // 2048 bins over [-4, 12)
-    return (int)fminf(fmaxf(x, 0.0f), 2047.0f);
-}
-
 template <int G, int KPT, int THREADS>
 __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
 {
@@ -450,11 +516,24 @@ tri_status launch_select_g(const SelectArgs &sa, int n_inst, hipStream_t st)
         hipLaunchKernelGGL((select_reg_kernel<G, 32, kSelThreads>), dim3(n_inst), dim3(kSelThreads), 0, st, sa);
         return hip_status("select_reg_kernel");
     }
+    // Longer than the register-resident kernel takes.  Two launches split the head-instances by length on the
+    // device: those whose keys fit LDS, and the rest, whose keys go through the workspace -- that launch asks for no
+    // dynamic LDS, so two workgroups share a CU and one's load phase overlaps the other's ranking and emit.
     auto kern = select_kernel<G>;
-    const size_t lds = (size_t)sa.lds_keys * sizeof(uint32_t);
+    const size_t lds = (size_t)kSelLdsKeys * sizeof(uint32_t);
     if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return hip_status("hipFuncSetAttribute(select_kernel)");
-    hipLaunchKernelGGL(kern, dim3(n_inst), dim3(kSelThreads), lds, st, sa);
+    SelectArgs lo = sa, hi = sa;
+    lo.lds_keys = kSelLdsKeys;
+    lo.n_above = -1;
+    lo.n_upto = kSelLdsKeys;
+    hi.lds_keys = 0;
+    hi.n_above = kSelLdsKeys;
+    hi.n_upto = sa.max_seq_len;
+    hipLaunchKernelGGL(kern, dim3(n_inst), dim3(kSelThreads), lds, st, lo);
+    tri_status rc = hip_status("select_kernel");
+    if (rc != TRI_OK) return rc;
+    hipLaunchKernelGGL(kern, dim3(n_inst), dim3(kSelThreads), 0, st, hi);
     return hip_status("select_kernel");
 }
 
@@ -468,7 +547,7 @@ tri_status launch_select(const tri_model &m, const float *final_scores, const fl
     if (n_inst <= 0) return TRI_OK;
     SelectArgs sa{final_scores, raw, stats, scratch, c.seq_len, kept_idx, kept_cnt, c.n_seqs, m.n_kv_heads,
                   c.max_seq_len, budget, c.max_seq_len < kSelLdsKeys ? (c.max_seq_len > 0 ? c.max_seq_len : 1) : kSelLdsKeys,
-                  m.head_budgets};
+                  m.head_budgets, -1, c.max_seq_len};
     if (final_scores) return launch_select_g<0>(sa, n_inst, st);
     switch (m.n_q_heads / m.n_kv_heads) {
         case 1: return launch_select_g<1>(sa, n_inst, st);
