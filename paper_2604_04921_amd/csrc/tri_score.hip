@@ -23,6 +23,9 @@ struct FoldArgs {
     double *band_rev;       // [F]
     double *phasors;        // [1 + S][F][2]: (0) mean over the offsets of e^{i w delta}; (1 + s) e^{i w cur_pos[s]}
     const int32_t *cur_pos; // [S]
+    const int32_t *seq_len; // [S]
+    int32_t *work;          // work list of the MFMA score kernel, or NULL when the generic kernel runs
+    int32_t max_seq_len;
     int32_t S, Hq, Hkv, G;
     double theta;
     int32_t n_off;
@@ -40,9 +43,14 @@ __device__ __forceinline__ void unit_phasor(double t, double rev, double *c, dou
 
 // The phasors the fold needs depend on the band and, for the query position, on the sequence only: they
 // are evaluated once here (double-precision pow / sincos are long software routines) instead of once per
-// query head and layer.  grid (1 + S), block F: thread = band.
+// query head and layer.  grid (2 + S), block F: thread = band.  The last workgroup has nothing to do with phasors:
+// it lists the chunks of the MFMA score kernel (a launch of its own would cost more than the list).
 __global__ __launch_bounds__(kBands) void fold_phasor_kernel(FoldArgs a)
 {
+    if ((int)blockIdx.x == a.S + 1) {   // uniform over the workgroup
+        if (a.work) build_work_list(a.seq_len, a.S, a.max_seq_len, a.work);
+        return;
+    }
     const int f = threadIdx.x;
     // Section 2.1: omega_f = theta^(-2f/d); kept as revolutions per position
     const double rev = pow(a.theta, -2.0 * (double)f / (double)kHeadDim) / kTwoPi;
@@ -348,14 +356,19 @@ tri_status launch_score_kernel(const tri_model &m, const ScoreArgs &sa, dim3 gri
     return hip_status("score_kernel");
 }
 
+// MFMA kernel: bf16, a group of 16 slots never straddling a block, 32-bit row offsets
+bool mfma_path(const tri_cache &c, int G)
+{
+    return c.dtype == TRI_BF16 && (c.block_size == 0 || c.block_size >= 16) &&
+           c.stride_slot * 2 * 16 < ((int64_t)1 << 31) && ((int64_t)G * c.max_seq_len + 16) * 4 < ((int64_t)1 << 32);
+}
+
 template <int G>
 tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, const FinalArgs &fa,
                           float *final_out, hipStream_t st)
 {
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
-    // MFMA kernel: bf16, a group of 16 slots never straddling a block, 32-bit row offsets
-    const bool fast = c.dtype == TRI_BF16 && (c.block_size == 0 || c.block_size >= 16) &&
-                      c.stride_slot * 2 * 16 < ((int64_t)1 << 31) && ((int64_t)G * c.max_seq_len + 16) * 4 < ((int64_t)1 << 32);
+    const bool fast = mfma_path(c, G);
     const int tile_keys = fast ? kFastChunk : kScoreTile;
     sa.n_tiles = (c.max_seq_len + tile_keys - 1) / tile_keys;
     tri_status rc = TRI_OK;
@@ -396,6 +409,9 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     fo.band_rev = reinterpret_cast<double *>(ws + wl.band_rev);
     fo.phasors = reinterpret_cast<double *>(ws + wl.fold_phasors);
     fo.cur_pos = c.cur_pos;
+    fo.seq_len = c.seq_len;
+    fo.work = mfma_path(c, G) ? reinterpret_cast<int32_t *>(ws + wl.work) : nullptr;
+    fo.max_seq_len = c.max_seq_len;
     fo.S = c.n_seqs;
     fo.Hq = m.n_q_heads;
     fo.Hkv = m.n_kv_heads;
@@ -404,7 +420,7 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     fo.n_off = m.n_offsets;
     fo.variant = m.score_variant;
     for (int j = 0; j < m.n_offsets; ++j) fo.offsets[j] = m.offsets[j];
-    hipLaunchKernelGGL(fold_phasor_kernel, dim3(1 + c.n_seqs), dim3(kBands), 0, st, fo);
+    hipLaunchKernelGGL(fold_phasor_kernel, dim3(2 + c.n_seqs), dim3(kBands), 0, st, fo);
     tri_status rc0 = hip_status("fold_phasor_kernel");
     if (rc0 != TRI_OK) return rc0;
     hipLaunchKernelGGL(fold_kernel, dim3(m.n_kv_heads, m.n_layers, (c.n_seqs + kFoldSeqs - 1) / kFoldSeqs),

@@ -27,13 +27,44 @@ constexpr int kPhasorBlockStride = kPhasorRange * 16 + 64;      // bytes per 4-b
 constexpr int kPhasorHalfStride = 16 * kPhasorBlockStride;      // bytes per half (bands 0-1 / 2-3 of a chunk)
 constexpr int kPhasorBytes = 2 * kPhasorHalfStride;
 
+// Work list of the MFMA score kernel, built on the device from the sequence lengths by one workgroup of any size
+// (kWorkThreads at most): [0] the kernel's shared item counter (zeroed here), [1] entries per (layer, KV head), from
+// kWorkHeader on one (sequence, chunk) pair per chunk of kFastChunk keys that exists.
+constexpr int kWorkHeader = 4;
+constexpr int kWorkThreads = 256;
+__device__ __forceinline__ void build_work_list(const int32_t *seq_len, int n_seqs, int max_seq_len, int32_t *work)
+{
+    __shared__ int start[kWorkThreads + 1];
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int seg = (n_seqs + nt - 1) / nt, s0 = min(n_seqs, tid * seg), s1 = min(n_seqs, s0 + seg);
+    int cnt = 0;
+    for (int s = s0; s < s1; ++s) cnt += (clamp_len(seq_len[s], max_seq_len) + kFastChunk - 1) / kFastChunk;
+    start[tid + 1] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+        start[0] = 0;
+        for (int k = 1; k <= nt; ++k) start[k] += start[k - 1];
+        work[0] = 0;
+        work[1] = start[nt];
+    }
+    __syncthreads();
+    int o = start[tid];
+    for (int s = s0; s < s1; ++s) {
+        const int n = (clamp_len(seq_len[s], max_seq_len) + kFastChunk - 1) / kFastChunk;
+        for (int ch = 0; ch < n; ++ch, ++o) {
+            work[kWorkHeader + 2 * o] = s;
+            work[kWorkHeader + 2 * o + 1] = ch;
+        }
+    }
+}
+
 tri_status launch_phasor_table(double theta, uint4 *phasors, hipStream_t st);
 // bf16 keys; G in 1..8
 tri_status launch_score_fast(int G, const ScoreArgs &sa, bool half_split, hipStream_t st);
 // ints the MFMA kernel's work list takes: a header and one (sequence, chunk) pair per possible chunk
 inline size_t fast_work_ints(int64_t n_seqs, int64_t max_seq_len)
 {
-    return 4 + 2 * (size_t)n_seqs * (size_t)((max_seq_len + kFastChunk - 1) / kFastChunk);
+    return kWorkHeader + 2 * (size_t)n_seqs * (size_t)((max_seq_len + kFastChunk - 1) / kFastChunk);
 }
 
 }  // namespace tri

@@ -150,41 +150,9 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
     for (int q = 0; q < NG; ++q) out[q] = reduce_blocks(acc[q]);
 }
 
-// One entry of the work list per (sequence, chunk of kFastChunk keys) that exists, written by work_list_kernel
-// from the sequence lengths on the device: [0] next item (the kernel's shared counter), [1] entries per
-// (layer, KV head), then (sequence, chunk) pairs.
-constexpr int kWorkHeader = 4;
-
-// grid 1, block 256
-__global__ __launch_bounds__(256) void work_list_kernel(const int32_t *seq_len, int n_seqs, int max_seq_len, int32_t *work)
-{
-    __shared__ int start[257];
-    const int tid = threadIdx.x;
-    const int seg = (n_seqs + 255) / 256, s0 = min(n_seqs, tid * seg), s1 = min(n_seqs, s0 + seg);
-    int cnt = 0;
-    for (int s = s0; s < s1; ++s) cnt += (clamp_len(seq_len[s], max_seq_len) + kFastChunk - 1) / kFastChunk;
-    start[tid + 1] = cnt;
-    __syncthreads();
-    if (tid == 0) {
-        start[0] = 0;
-        for (int k = 1; k <= 256; ++k) start[k] += start[k - 1];
-        work[0] = 0;
-        work[1] = start[256];
-    }
-    __syncthreads();
-    int o = start[tid];
-    for (int s = s0; s < s1; ++s) {
-        const int n = (clamp_len(seq_len[s], max_seq_len) + kFastChunk - 1) / kFastChunk;
-        for (int ch = 0; ch < n; ++ch, ++o) {
-            work[kWorkHeader + 2 * o] = s;
-            work[kWorkHeader + 2 * o + 1] = ch;
-        }
-    }
-}
-
 // grid = as many workgroups as the GPU holds at once, block 512 (768 for G > 4).  A workgroup stays for the whole launch and
-// takes items -- one (layer, KV head, sequence, chunk of 8192 keys) each -- from a shared counter until they run
-// out; the phasor table is loaded once per workgroup, and neither empty chunks of short sequences nor the order
+// takes items -- one (layer, KV head, sequence, chunk of 8192 keys) each, listed by build_work_list() -- from a
+// shared counter until they run out; the phasor table is loaded once per workgroup, and neither empty chunks of short sequences nor the order
 // in which the hardware hands workgroups to the XCDs cost anything (with one workgroup per chunk slot of the
 // longest sequence, ragged batches lost up to a quarter of the kernel's throughput to the empty ones).  The item's
 // keys are split evenly over the waves; each wave walks its contiguous share in groups of 16 (4 steps).
@@ -210,8 +178,8 @@ __global__ __launch_bounds__(fast_threads(G)) void score_mfma_kernel(ScoreArgs a
     if (tid < kBands) lds_rev[tid] = a.band_rev[tid];
     const int per_lh = __builtin_amdgcn_readfirstlane(a.work[1]);   // items per (layer, KV head)
     const int n_items = per_lh * a.n_layers * c.n_kv_heads;       // below 2^31: checked on the host
-    int next_item = 0;
-    if (tid == 0) next_item = atomicAdd(&a.work[0], 1);
+    // the first item is the workgroup's own index; later ones come from the shared counter, which starts at 0
+    int next_item = blockIdx.x;
 
   for (;;) {
     // every wave has finished the previous item when it arrives here: lds_tab, red and lds_item are free
@@ -219,7 +187,7 @@ __global__ __launch_bounds__(fast_threads(G)) void score_mfma_kernel(ScoreArgs a
     __syncthreads();
     const int item = __builtin_amdgcn_readfirstlane(lds_item);
     if (item >= n_items) break;   // uniform over the workgroup; the counter only grows, so every workgroup gets here
-    if (tid == 0) next_item = atomicAdd(&a.work[0], 1);   // in flight while this item is scored
+    if (tid == 0) next_item = (int)gridDim.x + atomicAdd(&a.work[0], 1);   // in flight while this item is scored
     const int lh = item / per_lh, wi = item - lh * per_lh;
     const int l = lh / c.n_kv_heads, h = lh - l * c.n_kv_heads;
     const int s = __builtin_amdgcn_readfirstlane(a.work[kWorkHeader + 2 * wi]);
@@ -571,7 +539,6 @@ tri_status launch_fast_g(const ScoreArgs &sa, bool half_split, hipStream_t st)
         return TRI_ERR_UNSUPPORTED;
     }
     const int grid = (int)std::min<int64_t>((int64_t)slots, max_items);
-    hipLaunchKernelGGL(work_list_kernel, dim3(1), dim3(256), 0, st, sa.c.seq_len, sa.c.n_seqs, sa.c.max_seq_len, sa.work);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(fast_threads(G)), lds, st, sa);
     return hip_status("score_mfma_kernel");
 }
