@@ -13,6 +13,7 @@ struct ScoreArgs {
     double *partials;        // [L][S][Hkv][n_tiles][2G]: per-tile sum and sum of squares
     int32_t n_tiles;         // tiles per head-instance in `partials`
     int32_t n_layers;
+    int32_t first_mult;      // MFMA kernel only: workgroup b starts on item (b * first_mult) mod grid size
     int32_t *work;           // MFMA kernel only: item counter and work list (kFastWorkInts(S, Nmax) ints)
 };
 

@@ -178,8 +178,14 @@ __global__ __launch_bounds__(fast_threads(G)) void score_mfma_kernel(ScoreArgs a
     if (tid < kBands) lds_rev[tid] = a.band_rev[tid];
     const int per_lh = __builtin_amdgcn_readfirstlane(a.work[1]);   // items per (layer, KV head)
     const int n_items = per_lh * a.n_layers * c.n_kv_heads;       // below 2^31: checked on the host
-    // the first item is the workgroup's own index; later ones come from the shared counter, which starts at 0
-    int next_item = blockIdx.x;
+    // The first item needs no trip to the shared counter (hundreds of workgroups asking at once queue up on that one
+    // address for tens of microseconds, which is what a small batch takes in all): workgroup b starts on item
+    // (b * first_mult) mod gridDim.x, a permutation (first_mult is coprime to the grid size); later items are
+    // gridDim.x + the counter's value.  The identity (item b) was measured 4 to 11 % slower on the large
+    // configurations than this or than a counter-only start; why is not understood -- workgroups go to the XCDs
+    // round-robin by index, so the identity ties neighbouring items to neighbouring XCDs in the first round and,
+    // with equal item durations, in every later one.
+    int next_item = (int)(((uint32_t)blockIdx.x * (uint32_t)a.first_mult) % gridDim.x);
 
   for (;;) {
     // every wave has finished the previous item when it arrives here: lds_tab, red and lds_item are free
@@ -539,7 +545,14 @@ tri_status launch_fast_g(const ScoreArgs &sa, bool half_split, hipStream_t st)
         return TRI_ERR_UNSUPPORTED;
     }
     const int grid = (int)std::min<int64_t>((int64_t)slots, max_items);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(fast_threads(G)), lds, st, sa);
+    ScoreArgs sb = sa;
+    sb.first_mult = 1;
+    for (int p : {197, 199, 211, 223})   // a prime that does not divide the grid size
+        if (grid % p != 0) {
+            sb.first_mult = p;
+            break;
+        }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(fast_threads(G)), lds, st, sb);
     return hip_status("score_mfma_kernel");
 }
 
