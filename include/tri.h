@@ -163,7 +163,9 @@ size_t tri_workspace_size(const tri_model *model, const tri_cache *cache, int32_
  *              n >= N_s are not written
  *   raw_out    NULL, or device [n_layers][n_seqs][n_q_heads][max_seq_len] float: S~(g), query
  *              head h*G+g belonging to KV head h
- *   workspace  device, 256-byte aligned, ws_bytes >= tri_workspace_size(); contents undefined after
+ *   workspace  device, 256-byte aligned, ws_bytes >= tri_workspace_size(); contents undefined after.
+ *              It holds tables, partial sums and the score kernel's work list and item counter: calls that
+ *              may overlap in time (different streams) need a workspace each
  * sigma is the population standard deviation; a head with sigma = 0 contributes 0 to the maximum.
  */
 tri_status tri_score(const tri_model *model, const float *centers, const tri_cache *cache,
