@@ -158,7 +158,8 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
 // keys are split evenly over the waves; each wave walks its contiguous share in groups of 16 (4 steps).
 // PAGED: block_size >= 16, so a group never straddles a block.
 template <int G, bool PAGED, bool ROTATED, bool HALF>
-__global__ __launch_bounds__(fast_threads(G)) void score_mfma_kernel(ScoreArgs a)
+// (the second launch bound keeps every variant at four waves per SIMD for G <= 4, three above: two workgroups per CU)
+__global__ __launch_bounds__(fast_threads(G), G > 4 ? 3 : 4) void score_mfma_kernel(ScoreArgs a)
 {
     constexpr int NG = (G + 3) / 4;
     constexpr int kFastThreads = fast_threads(G), kFastWaves = kFastThreads / 64;
