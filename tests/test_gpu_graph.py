@@ -65,3 +65,43 @@ def test_compress_step_in_a_graph(oracle, fill):
         got = outputs()
         for a, b in zip(got, eager[shifts.index(sh)]):
             assert torch.equal(a, b), "replay %d (shift %d) differs from the eager result" % (rep, sh)
+
+
+def test_two_calls_on_two_streams():
+    """Two tri_compress_step calls in flight at once on two streams, each with its own workspace (the score kernel's
+    item counter and work list live there): both give what they give one after the other."""
+    cfgs = [recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=2, n_seqs=3, n_q_heads=8, n_kv_heads=2, seq_len=20000,
+                          min_seq_len=3000, budget=512, n_calib=128, seed=recipe.SEED_BASE + 40 + i) for i in range(2)]
+    runs = []
+    for cfg in cfgs:
+        run = GpuRun(cfg, recipe.generate(cfg))
+        run.build_centers()
+        kd, vd, pd = torch.zeros_like(run.k), torch.zeros_like(run.v), torch.zeros_like(run.pos)
+        run.dst_tensors = (kd, vd, pd)
+        run.dst = run.B.Cache(kd, vd, pd, run.seq_len, run.cur_pos, run.nmax)
+        runs.append(run)
+
+    def launch(run, stream=None):
+        run.B.tri_compress_step(run.model, run.centers, run.cache, run.dst, run.cfg.budget, run.kept_idx, run.kept_cnt,
+                                run.new_len, run.ws, stream=stream)
+
+    def outputs(run):
+        return [t.clone() for t in (run.kept_idx, run.kept_cnt, run.new_len) + run.dst_tensors]
+
+    serial = []
+    for run in runs:
+        launch(run)
+        torch.cuda.synchronize()
+        serial.append(outputs(run))
+        for t in (run.kept_idx, run.kept_cnt, run.new_len) + run.dst_tensors:
+            t.fill_(0)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for s in streams:
+        s.wait_stream(torch.cuda.current_stream())
+    for rep in range(3):
+        for run, s in zip(runs, streams):
+            launch(run, stream=s)
+    torch.cuda.synchronize()
+    for run, ref in zip(runs, serial):
+        for a, b in zip(outputs(run), ref):
+            assert torch.equal(a, b)
