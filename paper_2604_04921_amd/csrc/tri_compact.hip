@@ -123,8 +123,8 @@ __global__ __launch_bounds__(kInplaceThreads) void inplace_kernel(CompactArgs a)
             const int j = j0 + u * rows_per_pass + r;
             if (src_n[u] >= 0 && src_n[u] != j) {
                 const int64_t so = kv_offset(a.src, l, s, h, src_n[u]) * a.elem_bytes + part * 16;
-                kv[u] = *reinterpret_cast<const uint4 *>(kb + so);
-                vv[u] = *reinterpret_cast<const uint4 *>(vb + so);
+                kv[u] = load_stream16(kb + so);
+                vv[u] = load_stream16(vb + so);
                 if (part == 0) pp[u] = pb[pos_offset(a.src, l, s, h, src_n[u])];
             }
         }
@@ -136,8 +136,8 @@ __global__ __launch_bounds__(kInplaceThreads) void inplace_kernel(CompactArgs a)
             const int j = j0 + u * rows_per_pass + r;
             if (src_n[u] >= 0 && src_n[u] != j) {
                 const int64_t d_o = kv_offset(a.dst, l, s, h, j) * a.elem_bytes + part * 16;
-                *reinterpret_cast<uint4 *>(kb + d_o) = kv[u];
-                *reinterpret_cast<uint4 *>(vb + d_o) = vv[u];
+                store_stream16(kb + d_o, kv[u]);
+                store_stream16(vb + d_o, vv[u]);
                 if (part == 0) pb[pos_offset(a.dst, l, s, h, j)] = pp[u];
             }
         }
