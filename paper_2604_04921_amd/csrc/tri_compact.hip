@@ -225,10 +225,10 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(CompactArgs a)
         const int dj = moves[m], sn = moves[a.budget + m];
         const int64_t so = kv_offset(a.src, l, s, h, sn) * a.elem_bytes + part * 16;
         const int64_t d_o = kv_offset(a.dst, l, s, h, dj) * a.elem_bytes + part * 16;
-        const uint4 kv = *reinterpret_cast<const uint4 *>(kb + so);
-        const uint4 vv = *reinterpret_cast<const uint4 *>(vb + so);
-        *reinterpret_cast<uint4 *>(kb + d_o) = kv;
-        *reinterpret_cast<uint4 *>(vb + d_o) = vv;
+        const uint4 kv = load_stream16(kb + so);
+        const uint4 vv = load_stream16(vb + so);
+        store_stream16(kb + d_o, kv);
+        store_stream16(vb + d_o, vv);
         if (part == 0) pb[pos_offset(a.dst, l, s, h, dj)] = pb[pos_offset(a.src, l, s, h, sn)];
     }
 }

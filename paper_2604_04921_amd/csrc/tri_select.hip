@@ -338,11 +338,12 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
                 if constexpr (G > 0) {
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
-                        const float z = z_score(rw[(int64_t)g * a.max_seq_len + nc], zp[g]);
+                        // raw scores are read exactly once
+                        const float z = z_score(__builtin_nontemporal_load(&rw[(int64_t)g * a.max_seq_len + nc]), zp[g]);
                         f = g == 0 ? z : fmaxf(f, z);
                     }
                 } else {
-                    f = fs[nc];
+                    f = __builtin_nontemporal_load(&fs[nc]);
                 }
                 key[j] = n < N ? order_key(f) : 0u;
             }
