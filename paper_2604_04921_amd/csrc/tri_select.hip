@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
         if constexpr (G > 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float z = z_score(rw[(int64_t)g * a.max_seq_len + n], zp[g]);
+                const float z = z_score(__builtin_nontemporal_load(&rw[(int64_t)g * a.max_seq_len + n]), zp[g]);
                 f = g == 0 ? z : fmaxf(f, z);
             }
         } else {
