@@ -22,7 +22,7 @@ STEP_BYTES = lambda n, b: 260 * n + 1032 * min(n, b)   # + survivors' K, V, pos 
 # HBM bytes of one score-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE in two runs,
 # each scaled by what the same counter reads for a plain device copy of known size: FETCH_SIZE reads 0.5 of the
 # bytes a 1 GiB copy fetches, WRITE_SIZE 1.0); summary in profiles/pmc_traffic_c3_model.md.
-MEASURED_TRAFFIC = {"c3_model/dense": 39.81e9 + 2.44e9}
+MEASURED_TRAFFIC = {"c3_model/dense": 39.80e9 + 2.43e9}
 
 
 def main():
