@@ -184,8 +184,8 @@ __global__ __launch_bounds__(fast_threads(G), G > 4 ? 3 : 4) void score_mfma_ker
     // (b * first_mult) mod gridDim.x, a permutation (first_mult is coprime to the grid size); later items are
     // gridDim.x + the counter's value.  The identity (item b) was measured 4 to 11 % slower on the large
     // configurations than this or than a counter-only start; why is not understood -- workgroups go to the XCDs
-    // round-robin by index, so the identity ties neighbouring items to neighbouring XCDs in the first round and,
-    // with equal item durations, in every later one.
+    // in turn by index, so the identity ties neighbouring items to neighbouring XCDs for the first items and, with
+    // equal item durations, for every later one.
     int next_item = (int)(((uint32_t)blockIdx.x * (uint32_t)a.first_mult) % gridDim.x);
 
   for (;;) {
