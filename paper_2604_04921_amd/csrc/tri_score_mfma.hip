@@ -120,32 +120,41 @@ __device__ __forceinline__ void score_step(const uint4 kd, const float (&cs)[4],
                                            const LaneTable (&tb)[NG], float (&out)[NG])
 {
     const uint32_t w[4] = {kd.x, kd.y, kd.z, kd.w};
+    // First everything the vector ALU does for the four bands, then the twelve matrix instructions in one run: a
+    // wave that alternates between the two kinds pays about 3.5 cycles per matrix instruction for it (measured with
+    // four waves per SIMD: 16 x (one 4x4x1 + two additions) take 115 ns per SIMD, 20 of the former followed by 32 of
+    // the latter 107 ns, which is the sum of their separate rates).
+    float kr[4], ki[4], m[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float re, im;
+        if constexpr (HALF) {
+            re = (k & 1) ? bf16_hi(w[k >> 1]) : bf16_lo(w[k >> 1]);
+            im = (k & 1) ? bf16_hi(w[2 + (k >> 1)]) : bf16_lo(w[2 + (k >> 1)]);
+        } else {
+            re = bf16_lo(w[k]);
+            im = bf16_hi(w[k]);
+        }
+        // |k_f|^2 from the unpacked pair: fp32 multiplications and fused multiply-adds run at twice the rate of the
+        // packed bf16 dot product (and of every integer, conversion or cross-lane instruction) on this GPU
+        m[k] = __builtin_amdgcn_sqrtf(fmaf(re, re, im * im));
+        kr[k] = ROTATE ? re * cs[k] - im * sn[k] : re;
+        ki[k] = ROTATE ? re * sn[k] + im * cs[k] : im;
+    }
+    __builtin_amdgcn_sched_barrier(0);
     float4v acc[NG];
 #pragma unroll
     for (int q = 0; q < NG; ++q) acc[q] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        float re, im, m;
-        if constexpr (HALF) {
-            re = (k & 1) ? bf16_hi(w[k >> 1]) : bf16_lo(w[k >> 1]);
-            im = (k & 1) ? bf16_hi(w[2 + (k >> 1)]) : bf16_lo(w[2 + (k >> 1)]);
-            m = __builtin_amdgcn_sqrtf(fmaf(re, re, im * im));
-        } else {
-            re = bf16_lo(w[k]);
-            im = bf16_hi(w[k]);
-            // |k_f|^2 straight from the packed bf16 pair (products of bf16 are exact in fp32)
-            const bf16x2 kk = __builtin_bit_cast(bf16x2, w[k]);
-            m = __builtin_amdgcn_sqrtf(__builtin_amdgcn_fdot2_f32_bf16(kk, kk, 0.0f, false));
-        }
-        const float kr = ROTATE ? re * cs[k] - im * sn[k] : re;
-        const float ki = ROTATE ? re * sn[k] + im * cs[k] : im;
 #pragma unroll
-        for (int q = 0; q < NG; ++q) {
-            acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(kr, tb[q].rr[k], acc[q], 0, 0, 0);
-            acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(ki, tb[q].ri[k], acc[q], 0, 0, 0);
-            acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(m, tb[q].cn[k], acc[q], 0, 0, 0);
-        }
+        for (int q = 0; q < NG; ++q) acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(kr[k], tb[q].rr[k], acc[q], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < NG; ++q) acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(ki[k], tb[q].ri[k], acc[q], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < NG; ++q) acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(m[k], tb[q].cn[k], acc[q], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int q = 0; q < NG; ++q) out[q] = reduce_blocks(acc[q]);
 }
