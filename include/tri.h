@@ -22,8 +22,10 @@
  *   - Return value: TRI_OK or a negative tri_status.  Nothing aborts or throws.
  *     tri_last_error() returns a static string describing the last failure on the calling thread.
  *   - Non-finite key or statistics values: behaviour undefined.
- *   - head_dim must be 128 (64 frequency bands); n_q_heads / n_kv_heads (= G) must be between 1 and 8;
- *     positions, cur_pos and cur_pos + max(offsets) must be below 2^62 in magnitude (positions
+ *   - Built geometries: head_dim 128 (64 frequency bands) and n_q_heads / n_kv_heads (= G) from 1 to 8; anything
+ *     else returns TRI_ERR_UNSUPPORTED.  n_layers and n_seqs * n_kv_heads must each be below 65536, and
+ *     head-instances x max(max_seq_len / 256, budget / 8) below 2^31 per call (TRI_ERR_UNSUPPORTED otherwise: split
+ *     the batch).  Positions, cur_pos and cur_pos + max(offsets) must be below 2^62 in magnitude (positions
  *     and cur_pos are int32).
  */
 #ifndef TRI_H
@@ -187,9 +189,11 @@ tri_status tri_select_topk(const tri_model *model, const float *final_scores,
 /*
  * Step 4: slot j of dst <- slot kept_idx[j] of src, for K, V and positions, j < kept_cnt.
  * dst may describe the same memory as src (in-place compaction; also for the paged layout,
- * where the survivors fill the sequence's first blocks and the caller frees the rest).  If
- * dst is a different cache it must not overlap src.  dst uses its own strides / block table
- * and src's n_seqs and dtype; dst->seq_len, cur_pos and max_seq_len are ignored.
+ * where the survivors fill the sequence's first blocks and the caller frees the rest): it must
+ * then be the same mapping -- the same k, v, pos, strides and block table -- or the call returns
+ * TRI_ERR_INVALID_ARG.  If dst is a different cache it must not overlap src; it uses its own strides / block
+ * table, needs room for min(max_seq_len, budget) slots per sequence only, and takes src's n_seqs and dtype;
+ * dst->seq_len, cur_pos and max_seq_len are ignored.
  *   new_seq_len  NULL or device [n_seqs] int32 <- min(N_s, budget)
  * kept_idx must be ascending and free of duplicates per head-instance (as tri_select_topk writes it);
  * otherwise the result is unspecified, but a count is read into [0, budget] and a slot index into

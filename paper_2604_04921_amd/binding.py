@@ -18,7 +18,8 @@ TRI_PAIR_INTERLEAVED, TRI_PAIR_HALF = 0, 1
 TRI_SCORE_FULL, TRI_SCORE_TRIG_ONLY, TRI_SCORE_NORM_ONLY, TRI_SCORE_NORM_UNWEIGHTED = 0, 1, 2, 3
 
 EXPORTS = ["tri_last_error", "tri_build_centers", "tri_centers_accumulate", "tri_centers_finalize", "tri_band_diagnostics", "tri_workspace_size", "tri_score", "tri_select_topk",
-           "tri_compact", "tri_compact_fill", "tri_compress_step", "tri_timing_attach", "tri_timing_detach"]
+           "tri_compact", "tri_compact_fill", "tri_compress_step",
+           "tri_timing_attach", "tri_timing_detach"]
 
 
 class TriModel(ctypes.Structure):

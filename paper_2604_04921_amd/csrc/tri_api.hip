@@ -1,6 +1,7 @@
 // C-ABI entry points: host-side validation and dispatch.  See include/tri.h for the contract.
 #include <cstdarg>
 #include <cstdio>
+#include <algorithm>
 
 #include "tri_internal.h"
 #include "tri_score_common.h"
@@ -183,6 +184,62 @@ Workspace workspace_layout(const tri_model &m, const tri_cache &c, int32_t budge
     return w;
 }
 
+// Sizes that the launch grids cannot take are refused here, before anything is enqueued.  Head-instances (times the
+// workgroups each of them gets) are a grid's x index, below 2^31; the score kernel for fp32 keys and small blocks puts
+// (sequence, KV head) on y and the layer on z, below 65536 each.
+tri_status check_limits(const tri_model &m, const tri_cache &c, int32_t budget, const char *what)
+{
+    const int64_t inst = (int64_t)m.n_layers * c.n_seqs * m.n_kv_heads;
+    const int64_t per_inst = std::max<int64_t>(((int64_t)c.max_seq_len + 255) / 256, ((int64_t)budget + 7) / 8);
+    if (inst * std::max<int64_t>(per_inst, 1) > (int64_t)0x7fffffff) {
+        set_error("%s: %lld head-instances of up to %d keys (budget %d) exceed what one call takes; split the batch",
+                  what, (long long)inst, c.max_seq_len, budget);
+        return TRI_ERR_UNSUPPORTED;
+    }
+    if ((int64_t)c.n_seqs * m.n_kv_heads > 65535 || m.n_layers > 65535) {
+        set_error("%s: n_seqs * n_kv_heads and n_layers must each be below 65536", what);
+        return TRI_ERR_UNSUPPORTED;
+    }
+    return TRI_OK;
+}
+
+// The checks of tri_compact on its two caches; *d receives dst completed with the fields it borrows from src.
+static tri_status check_compact(const tri_model *model, const tri_cache *src, const tri_cache *dst, int32_t budget,
+                                tri_cache *d, const char *what)
+{
+    if (!dst || !dst->k || !dst->v || !dst->pos) {
+        set_error("%s: dst with k, v, pos required", what);
+        return TRI_ERR_INVALID_ARG;
+    }
+    *d = *dst;
+    d->n_seqs = src->n_seqs;
+    d->dtype = src->dtype;
+    d->seq_len = src->seq_len;
+    d->cur_pos = src->cur_pos;
+    // only the first min(N_s, budget) slots of dst are ever written
+    d->max_seq_len = budget < src->max_seq_len ? budget : src->max_seq_len;
+    tri_status rc = check_cache(model, d, true, what);
+    if (rc != TRI_OK) return rc;
+    if (dst->k == src->k || dst->v == src->v || dst->pos == src->pos) {
+        // In place: the ordered move relies on dst slot j and src slot j being the same memory, so the two
+        // descriptors must map slots identically.
+        const bool same_map = dst->k == src->k && dst->v == src->v && dst->pos == src->pos &&
+                              dst->block_size == src->block_size && dst->block_table == src->block_table &&
+                              (dst->block_size == 0 || dst->max_blocks_per_seq == src->max_blocks_per_seq) &&
+                              dst->stride_layer == src->stride_layer && dst->stride_seq_or_block == src->stride_seq_or_block &&
+                              dst->stride_head == src->stride_head && dst->stride_slot == src->stride_slot &&
+                              dst->pos_stride_layer == src->pos_stride_layer &&
+                              dst->pos_stride_seq_or_block == src->pos_stride_seq_or_block &&
+                              dst->pos_stride_head == src->pos_stride_head;
+        if (!same_map) {
+            set_error("%s: dst shares memory with src but maps slots differently (in-place compaction needs the same "
+                      "k, v, pos, strides and block table)", what);
+            return TRI_ERR_INVALID_ARG;
+        }
+    }
+    return check_limits(*model, *src, budget, what);
+}
+
 static tri_status check_workspace(const Workspace &wl, void *ws, size_t ws_bytes)
 {
     if (!ws || ((uintptr_t)ws & 255) || ws_bytes < wl.total) {
@@ -296,6 +353,7 @@ tri_status tri_score(const tri_model *model, const float *centers, const tri_cac
         set_error("tri_score: centers and final_out required");
         return TRI_ERR_INVALID_ARG;
     }
+    if ((rc = check_limits(*model, *cache, 0, "tri_score")) != TRI_OK) return rc;
     const Workspace wl = workspace_layout(*model, *cache, 1);
     if ((rc = check_workspace(wl, workspace, ws_bytes)) != TRI_OK) return rc;
     return launch_score(*model, centers, *cache, final_out, raw_out, (char *)workspace, wl, (hipStream_t)stream);
@@ -317,6 +375,7 @@ tri_status tri_select_topk(const tri_model *model, const float *final_scores, co
         set_error("tri_select_topk: final_scores, kept_idx, kept_cnt and budget >= 1 required");
         return TRI_ERR_INVALID_ARG;
     }
+    if ((rc = check_limits(*model, *cache, budget, "tri_select_topk")) != TRI_OK) return rc;
     return launch_select(*model, final_scores, nullptr, nullptr, nullptr, *cache, budget, kept_idx, kept_cnt,
                          (hipStream_t)stream);
 }
@@ -327,25 +386,12 @@ tri_status tri_compact(const tri_model *model, const tri_cache *src, const tri_c
     tri_status rc = check_model(model);
     if (rc != TRI_OK) return rc;
     if ((rc = check_cache(model, src, true, "tri_compact src")) != TRI_OK) return rc;
-    if (!dst || !dst->k || !dst->v || !dst->pos) {
-        set_error("tri_compact: dst with k, v, pos required");
-        return TRI_ERR_INVALID_ARG;
-    }
-    tri_cache d = *dst;  // dst borrows the fields it does not own from src
-    d.n_seqs = src->n_seqs;
-    d.dtype = src->dtype;
-    d.seq_len = src->seq_len;
-    d.cur_pos = src->cur_pos;
-    d.max_seq_len = src->max_seq_len;
-    if ((rc = check_cache(model, &d, true, "tri_compact dst")) != TRI_OK) return rc;
-    if (d.block_size > 0 && (int64_t)d.max_blocks_per_seq * d.block_size < (budget < src->max_seq_len ? budget : src->max_seq_len)) {
-        set_error("tri_compact: dst block table too short for the budget");
-        return TRI_ERR_INVALID_ARG;
-    }
     if (!kept_idx || !kept_cnt || budget < 1) {
         set_error("tri_compact: kept_idx, kept_cnt and budget >= 1 required");
         return TRI_ERR_INVALID_ARG;
     }
+    tri_cache d;
+    if ((rc = check_compact(model, src, dst, budget, &d, "tri_compact")) != TRI_OK) return rc;
     return launch_compact(*model, *src, d, budget, kept_idx, kept_cnt, new_seq_len, (hipStream_t)stream);
 }
 
@@ -359,12 +405,15 @@ tri_status tri_compact_fill(const tri_model *model, const tri_cache *cache, int3
         set_error("tri_compact_fill: kept_idx, kept_cnt and budget >= 1 required");
         return TRI_ERR_INVALID_ARG;
     }
+    if ((rc = check_limits(*model, *cache, budget, "tri_compact_fill")) != TRI_OK) return rc;
+    if ((rc = check_fill_budget(budget)) != TRI_OK) return rc;
     return launch_compact_fill(*model, *cache, budget, kept_idx, kept_cnt, new_seq_len, (hipStream_t)stream);
 }
 
-tri_status tri_compress_step(const tri_model *model, const float *centers, const tri_cache *src,
-                             const tri_cache *dst, int32_t budget, int32_t *kept_idx, int32_t *kept_cnt,
-                             int32_t *new_seq_len, void *workspace, size_t ws_bytes, void *stream)
+// Everything tri_compress_step checks, so that an invalid call enqueues nothing at all: the source cache, the
+// destination (as tri_compact or tri_compact_fill will check it again, on the same arguments) and the grid limits.
+static tri_status check_step(const tri_model *model, const float *centers, const tri_cache *src, const tri_cache *dst,
+                             int32_t budget, const int32_t *kept_idx, const int32_t *kept_cnt)
 {
     tri_status rc = check_model(model);
     if (rc != TRI_OK) return rc;
@@ -373,9 +422,17 @@ tri_status tri_compress_step(const tri_model *model, const float *centers, const
         set_error("tri_compress_step: centers, kept_idx, kept_cnt and budget >= 1 required");
         return TRI_ERR_INVALID_ARG;
     }
-    const Workspace wl = workspace_layout(*model, *src, budget);
-    if ((rc = check_workspace(wl, workspace, ws_bytes)) != TRI_OK) return rc;
-    char *ws = (char *)workspace;
+    if ((rc = check_limits(*model, *src, budget, "tri_compress_step")) != TRI_OK) return rc;
+    if (!dst) return check_fill_budget(budget);
+    tri_cache d;
+    return check_compact(model, src, dst, budget, &d, "tri_compress_step dst");
+}
+
+static tri_status run_step(const tri_model *model, const float *centers, const tri_cache *src, const tri_cache *dst,
+                           int32_t budget, int32_t *kept_idx, int32_t *kept_cnt, int32_t *new_seq_len, char *ws,
+                           const Workspace &wl, void *stream)
+{
+    tri_status rc;
     // raw scores and their statistics stay in the workspace; the selection forms the final scores itself
     if ((rc = launch_score(*model, centers, *src, nullptr, nullptr, ws, wl, (hipStream_t)stream)) != TRI_OK) return rc;
     if ((rc = launch_select(*model, nullptr, reinterpret_cast<const float *>(ws + wl.raw),
@@ -385,6 +442,17 @@ tri_status tri_compress_step(const tri_model *model, const float *centers, const
         return rc;
     if (!dst) return tri_compact_fill(model, src, budget, kept_idx, kept_cnt, new_seq_len, stream);
     return tri_compact(model, src, dst, budget, kept_idx, kept_cnt, new_seq_len, stream);
+}
+
+tri_status tri_compress_step(const tri_model *model, const float *centers, const tri_cache *src,
+                             const tri_cache *dst, int32_t budget, int32_t *kept_idx, int32_t *kept_cnt,
+                             int32_t *new_seq_len, void *workspace, size_t ws_bytes, void *stream)
+{
+    tri_status rc = check_step(model, centers, src, dst, budget, kept_idx, kept_cnt);
+    if (rc != TRI_OK) return rc;
+    const Workspace wl = workspace_layout(*model, *src, budget);
+    if ((rc = check_workspace(wl, workspace, ws_bytes)) != TRI_OK) return rc;
+    return run_step(model, centers, src, dst, budget, kept_idx, kept_cnt, new_seq_len, (char *)workspace, wl, stream);
 }
 
 }  // extern "C"

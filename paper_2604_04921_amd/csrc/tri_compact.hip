@@ -14,6 +14,7 @@ struct CompactArgs {
     int32_t budget;
     int32_t row16;            // 16-byte chunks per K (or V) row
     int32_t elem_bytes;
+    int32_t row_blocks;       // gather kernel: workgroups per head-instance
 };
 
 __device__ __forceinline__ void decode_inst(const CacheView &c, int inst, int &l, int &s, int &h)
@@ -57,25 +58,26 @@ __device__ __forceinline__ uint4 load_stream16(const char *p)
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-// dst and src are different memory: a plain gather.  grid (ceil(B / rows per block), instances), block 128: the
-// row block is the fastest grid index, so workgroups that run together write neighbouring rows.
+// dst and src are different memory: a plain gather.  grid (instances * ceil(B / rows per block)), block 128: the
+// row block is the fastest part of the index, so workgroups that run together write neighbouring rows.
 // The workgroups are so small (one 16-byte piece of one row per thread) that their fixed cost matters -- the
 // kernel is bound by instruction issue, much of it integer division and 64-bit index arithmetic: two
 // divisions decode the instance, row16 is a power of two, and everything uniform stays in scalar registers.
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(CompactArgs a)
 {
-    const int inst = blockIdx.y;
+    // x = instance * row_blocks + row block (x reaches 2^31 - 1; y and z stop at 65535)
+    const int inst = blockIdx.x / a.row_blocks, rb = blockIdx.x - inst * a.row_blocks;
     const int ls = inst / a.src.n_kv_heads, h = inst - ls * a.src.n_kv_heads;
     const int l = ls / a.src.n_seqs, s = ls - l * a.src.n_seqs;
     const int cnt = read_cnt(a, inst);
-    if (blockIdx.x == 0) write_new_len(a, l, s, h, cnt);
+    if (rb == 0) write_new_len(a, l, s, h, cnt);
     const int row_shift = a.row16 == 16 ? 4 : 5;   // bf16 rows are 16 pieces of 16 bytes, fp32 rows 32
     const int rows_per_pass = kGatherThreads >> row_shift;
     const int r = threadIdx.x >> row_shift, part = threadIdx.x & (a.row16 - 1);
     const int32_t *idx = a.kept_idx + (int64_t)inst * a.budget;
     const char *sk = (const char *)a.src.k, *sv = (const char *)a.src.v;
     char *dk = (char *)a.dst.k, *dv = (char *)a.dst.v;
-    for (int j0 = blockIdx.x * kRowsPerBlock; j0 < (blockIdx.x + 1) * kRowsPerBlock; j0 += rows_per_pass) {
+    for (int j0 = rb * kRowsPerBlock; j0 < (rb + 1) * kRowsPerBlock; j0 += rows_per_pass) {
         const int j = j0 + r;
         if (j >= cnt) continue;
         const int n = read_slot(a, idx, j);
@@ -235,15 +237,22 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(CompactArgs a)
 
 }  // namespace
 
+tri_status check_fill_budget(int32_t budget)
+{
+    if (budget > kFillMaxWords * 32) {
+        set_error("tri_compact_fill: budget %d above %d", budget, kFillMaxWords * 32);
+        return TRI_ERR_UNSUPPORTED;
+    }
+    return TRI_OK;
+}
+
 tri_status launch_compact_fill(const tri_model &m, const tri_cache &c, int32_t budget, const int32_t *kept_idx,
                                const int32_t *kept_cnt, int32_t *new_seq_len, hipStream_t st)
 {
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
     if (n_inst <= 0) return TRI_OK;
-    if (budget > kFillMaxWords * 32) {
-        set_error("tri_compact_fill: budget %d above %d", budget, kFillMaxWords * 32);
-        return TRI_ERR_UNSUPPORTED;
-    }
+    tri_status rc = check_fill_budget(budget);
+    if (rc != TRI_OK) return rc;
     CompactArgs a{};
     a.src = make_view(m, c);
     a.dst = a.src;
@@ -282,8 +291,12 @@ tri_status launch_compact(const tri_model &m, const tri_cache &src, const tri_ca
         hipLaunchKernelGGL(inplace_kernel, dim3(n_inst), dim3(kInplaceThreads), 0, st, a);
         return hip_status("inplace_kernel");
     }
-    hipLaunchKernelGGL(gather_kernel, dim3((budget + kRowsPerBlock - 1) / kRowsPerBlock, n_inst), dim3(kGatherThreads), 0,
-                       st, a);
+    a.row_blocks = (budget + kRowsPerBlock - 1) / kRowsPerBlock;
+    if ((int64_t)a.row_blocks * n_inst > (int64_t)0x7fffffff) {
+        set_error("tri_compact: %d head-instances x %d row blocks exceed the grid", n_inst, a.row_blocks);
+        return TRI_ERR_UNSUPPORTED;
+    }
+    hipLaunchKernelGGL(gather_kernel, dim3((uint32_t)(a.row_blocks * (int64_t)n_inst)), dim3(kGatherThreads), 0, st, a);
     return hip_status("gather_kernel");
 }
 

@@ -95,6 +95,8 @@ Workspace workspace_layout(const tri_model &m, const tri_cache &c, int32_t budge
 void set_error(const char *fmt, ...);
 tri_status check_model(const tri_model *m);
 tri_status check_cache(const tri_model *m, const tri_cache *c, bool need_v, const char *what);
+tri_status check_limits(const tri_model &m, const tri_cache &c, int32_t budget, const char *what);
+tri_status check_fill_budget(int32_t budget);   // tri_compact_fill's own limit on the budget
 CacheView make_view(const tri_model &m, const tri_cache &c);
 tri_status hip_status(const char *what);
 // timing hook: the next event pair to record around a score-kernel launch, if any is attached

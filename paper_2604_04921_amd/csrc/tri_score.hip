@@ -298,16 +298,17 @@ struct FinalArgs {
     float *final_;        // [inst][Nmax]
     const int32_t *seq_len;
     int32_t n_seqs, n_kv_heads, max_seq_len;
+    int32_t key_blocks;   // workgroups per head-instance
 };
 
-// grid (ceil(Nmax/1024), instances), block 256: S_final(k) = max_g (S~(g)(k) - mu_g) / sigma_g.
+// grid (instances * ceil(Nmax/1024)), block 256: S_final(k) = max_g (S~(g)(k) - mu_g) / sigma_g.
 template <int G>
 __global__ __launch_bounds__(256) void final_kernel(FinalArgs a)
 {
-    const int inst = blockIdx.y;
+    const int inst = blockIdx.x / a.key_blocks, kb = blockIdx.x - inst * a.key_blocks;
     const int s = (inst / a.n_kv_heads) % a.n_seqs;
     const int N = clamp_len(a.seq_len[s], a.max_seq_len);
-    const int n = (blockIdx.x * 256 + threadIdx.x) * 4;
+    const int n = (kb * 256 + threadIdx.x) * 4;
     if (n >= N) return;
     const float *rw = a.raw + (int64_t)inst * G * a.max_seq_len + n;
     const double *st = a.stats + (int64_t)inst * G * 2;
@@ -390,7 +391,13 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
     hipLaunchKernelGGL(stats_kernel, dim3(n_inst), dim3(256), 0, st, ta);
     if ((rc = hip_status("stats_kernel")) != TRI_OK) return rc;
     if (final_out) {
-        hipLaunchKernelGGL(final_kernel<G>, dim3((c.max_seq_len + 1023) / 1024, n_inst), dim3(256), 0, st, fa);
+        FinalArgs fb = fa;
+        fb.key_blocks = (c.max_seq_len + 1023) / 1024;
+        if ((int64_t)fb.key_blocks * n_inst > (int64_t)0x7fffffff) {
+            set_error("tri_score: %d head-instances x %d key blocks exceed the grid", n_inst, fb.key_blocks);
+            return TRI_ERR_UNSUPPORTED;
+        }
+        hipLaunchKernelGGL(final_kernel<G>, dim3((uint32_t)((int64_t)fb.key_blocks * n_inst)), dim3(256), 0, st, fb);
         rc = hip_status("final_kernel");
     }
     return rc;
@@ -438,7 +445,7 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     sa.work = reinterpret_cast<int32_t *>(ws + wl.work);
     sa.n_layers = m.n_layers;
     FinalArgs fa{sa.raw, reinterpret_cast<double *>(ws + wl.stats), final_out, c.seq_len, c.n_seqs,
-                 m.n_kv_heads, c.max_seq_len};
+                 m.n_kv_heads, c.max_seq_len, 0};
     switch (G) {
         case 1: return launch_score_g<1>(m, c, sa, fa, final_out, st);
         case 2: return launch_score_g<2>(m, c, sa, fa, final_out, st);

@@ -17,6 +17,7 @@
 // A step whose four keys span R positions or more takes the direct path instead (phase in double,
 // v_sin_f32 / v_cos_f32), so any position layout is handled.
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "tri_score_common.h"
@@ -26,6 +27,7 @@ namespace tri {
 namespace {
 
 constexpr double kTwoPi = 6.283185307179586476925286766559;
+constexpr int kMaxDevices = 64;   // GPUs of one process the occupancy cache distinguishes
 // Workgroup size of the score kernel: with more than four query heads per KV head a wave needs more than 128
 // registers, so only three waves fit a SIMD; 12-wave workgroups fill them (8-wave ones would leave one of three unused).
 constexpr int fast_threads(int G) { return G > 4 ? 768 : 512; }
@@ -534,13 +536,20 @@ tri_status launch_fast_g(const ScoreArgs &sa, bool half_split, hipStream_t st)
     const int lds = sa.c.k_rotated ? 0 : kPhasorBytes;   // no phasor table for post-RoPE keys
     if (lds && hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return hip_status("hipFuncSetAttribute(score_mfma_kernel)");
-    // as many workgroups as are resident at once (they stay until the work list is empty), no more than items can exist
-    static int resident[2][2][2];   // per kernel of this G: asked once (all GPUs of a process are the same model)
-    int &slots = resident[sa.c.k_rotated ? 1 : 0][paged ? 1 : 0][half_split ? 1 : 0];
+    // as many workgroups as are resident at once (they stay until the work list is empty), no more than items can exist.
+    // The answer is kept per kernel and per GPU; threads that ask at the same time compute the same number.
+    static std::atomic<int> resident[2][2][2][kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        set_error("score: no current device below %d", kMaxDevices);
+        return TRI_ERR_HIP;
+    }
+    std::atomic<int> &cached = resident[sa.c.k_rotated ? 1 : 0][paged ? 1 : 0][half_split ? 1 : 0][dev];
+    int slots = cached.load(std::memory_order_relaxed);
     if (slots == 0) {
-        int dev = 0, n_cu = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        int n_cu = 0, per_cu = 0;
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kern, fast_threads(G), lds) != hipSuccess ||
             n_cu <= 0 || per_cu <= 0) {
             (void)hipGetLastError();
@@ -548,6 +557,7 @@ tri_status launch_fast_g(const ScoreArgs &sa, bool half_split, hipStream_t st)
             return TRI_ERR_HIP;
         }
         slots = n_cu * per_cu;
+        cached.store(slots, std::memory_order_relaxed);
     }
     const int64_t max_items = (int64_t)sa.n_tiles * sa.c.n_seqs * sa.c.n_kv_heads * sa.n_layers;
     if (max_items > (int64_t)0x7fff0000) {   // the item counter is a 32-bit integer
