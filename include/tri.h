@@ -226,6 +226,21 @@ tri_status tri_compress_step(const tri_model *model, const float *centers, const
                              size_t ws_bytes, void *stream);
 
 /*
+ * tri_compress_step for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace)
+ * and the same results as tri_compress_step; the scratch memory is an array inside the library,
+ * tri_static_scratch_size() bytes (64 MiB) on every GPU the library is used on, held until the process ends.
+ * The call allocates nothing (no hipMalloc / hipFree, no allocating library routine); a call whose
+ * tri_workspace_size() exceeds the array returns TRI_ERR_WORKSPACE and enqueues nothing.  Every call on a GPU uses
+ * that GPU's one array: two calls that may overlap in time on one GPU (different streams or threads) race --
+ * serialise them, or give the second one tri_compress_step with a workspace of its own.
+ */
+size_t tri_static_scratch_size(void);
+tri_status tri_compress_step_static(const tri_model *model, const float *centers, const tri_cache *src,
+                                    const tri_cache *dst, int32_t budget, int32_t *kept_idx,
+                                    int32_t *kept_cnt, int32_t *new_seq_len, void *stream);
+
+/*
  * Measurement hook for benchmark harnesses (no counterpart in the paper).  After attaching, the
  * i-th launch of the score kernel made by the calling thread (i = 0, 1, ...) is bracketed by
  * hipEventRecord(events[2i]) before and hipEventRecord(events[2i+1]) after it, on the stream of

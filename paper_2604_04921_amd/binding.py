@@ -18,7 +18,7 @@ TRI_PAIR_INTERLEAVED, TRI_PAIR_HALF = 0, 1
 TRI_SCORE_FULL, TRI_SCORE_TRIG_ONLY, TRI_SCORE_NORM_ONLY, TRI_SCORE_NORM_UNWEIGHTED = 0, 1, 2, 3
 
 EXPORTS = ["tri_last_error", "tri_build_centers", "tri_centers_accumulate", "tri_centers_finalize", "tri_band_diagnostics", "tri_workspace_size", "tri_score", "tri_select_topk",
-           "tri_compact", "tri_compact_fill", "tri_compress_step",
+           "tri_compact", "tri_compact_fill", "tri_compress_step", "tri_static_scratch_size", "tri_compress_step_static",
            "tri_timing_attach", "tri_timing_detach"]
 
 
@@ -83,6 +83,11 @@ def lib():
         L.tri_compress_step.restype = i32
         L.tri_compress_step.argtypes = [ctypes.POINTER(TriModel), vp, ctypes.POINTER(TriCache),
                                         ctypes.POINTER(TriCache), i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.tri_static_scratch_size.restype = ctypes.c_size_t
+        L.tri_static_scratch_size.argtypes = []
+        L.tri_compress_step_static.restype = i32
+        L.tri_compress_step_static.argtypes = [ctypes.POINTER(TriModel), vp, ctypes.POINTER(TriCache),
+                                               ctypes.POINTER(TriCache), i32, vp, vp, vp, vp]
         L.tri_timing_attach.restype = i32
         L.tri_timing_attach.argtypes = [vp, i32]
         L.tri_timing_detach.restype = i32
@@ -213,6 +218,16 @@ def tri_compress_step(model, centers, src, dst, budget, kept_idx, kept_cnt, new_
     _check(lib().tri_compress_step(model.ref, _p(centers), src.ref, dst.ref if dst is not None else None, int(budget), _p(kept_idx), _p(kept_cnt),
                                    _p(new_seq_len), _p(workspace), workspace.numel() * workspace.element_size(),
                                    _stream(stream)))
+
+
+def tri_static_scratch_size():
+    return int(lib().tri_static_scratch_size())
+
+
+def tri_compress_step_static(model, centers, src, dst, budget, kept_idx, kept_cnt, new_seq_len, stream=None):
+    """tri_compress_step on the library's own scratch array: no workspace argument, no allocation."""
+    _check(lib().tri_compress_step_static(model.ref, _p(centers), src.ref, dst.ref if dst is not None else None, int(budget),
+                                          _p(kept_idx), _p(kept_cnt), _p(new_seq_len), _stream(stream)))
 
 
 def tri_timing_attach(events):

@@ -2,6 +2,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <algorithm>
+#include <mutex>
 
 #include "tri_internal.h"
 #include "tri_score_common.h"
@@ -249,6 +250,39 @@ static tri_status check_workspace(const Workspace &wl, void *ws, size_t ws_bytes
     return TRI_OK;
 }
 
+// ---- scratch memory of tri_compress_step_static(): owned by the library, one copy per GPU, kept until the process ends
+constexpr size_t kStaticScratchBytes = TRI_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, asked once per GPU
+
+// The array's name is a host-side stand-in, not a device address: the address on the current GPU comes from the
+// runtime (no allocation: the array is part of the loaded code object).
+static tri_status static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        set_error("tri_compress_step_static: no current device below %d", kMaxDevices);
+        return TRI_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            set_error("tri_compress_step_static: hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+            return TRI_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return TRI_OK;
+}
+
 }  // namespace tri
 
 using namespace tri;
@@ -453,6 +487,25 @@ tri_status tri_compress_step(const tri_model *model, const float *centers, const
     const Workspace wl = workspace_layout(*model, *src, budget);
     if ((rc = check_workspace(wl, workspace, ws_bytes)) != TRI_OK) return rc;
     return run_step(model, centers, src, dst, budget, kept_idx, kept_cnt, new_seq_len, (char *)workspace, wl, stream);
+}
+
+size_t tri_static_scratch_size(void) { return kStaticScratchBytes; }
+
+tri_status tri_compress_step_static(const tri_model *model, const float *centers, const tri_cache *src,
+                                    const tri_cache *dst, int32_t budget, int32_t *kept_idx, int32_t *kept_cnt,
+                                    int32_t *new_seq_len, void *stream)
+{
+    tri_status rc = check_step(model, centers, src, dst, budget, kept_idx, kept_cnt);
+    if (rc != TRI_OK) return rc;
+    const Workspace wl = workspace_layout(*model, *src, budget);
+    if (wl.total > kStaticScratchBytes) {
+        set_error("tri_compress_step_static: this call needs %zu bytes of scratch, the library's own array holds %zu; "
+                  "use tri_compress_step with a workspace", wl.total, kStaticScratchBytes);
+        return TRI_ERR_WORKSPACE;
+    }
+    void *ws = nullptr;
+    if ((rc = static_scratch(&ws)) != TRI_OK) return rc;
+    return run_step(model, centers, src, dst, budget, kept_idx, kept_cnt, new_seq_len, (char *)ws, wl, stream);
 }
 
 }  // extern "C"

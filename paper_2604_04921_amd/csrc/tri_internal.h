@@ -15,6 +15,11 @@ constexpr int kScoreTile = 256;   // keys scored by one workgroup
 constexpr int kMaxOffsets = 64;
 constexpr int kMaxGroup = 8;
 
+// Bytes of the library's own scratch array (tri_compress_step_static), one copy per GPU.
+#ifndef TRI_STATIC_SCRATCH_BYTES
+#define TRI_STATIC_SCRATCH_BYTES (64u << 20)
+#endif
+
 // Device-side view of a tri_cache (plain copy of the descriptor's fields).
 struct CacheView {
     const void *k;

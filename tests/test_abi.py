@@ -108,3 +108,18 @@ def test_limits_and_in_place_rules_are_checked_before_anything_is_enqueued():
     assert L.tri_compress_step(ctypes.byref(m), 0x60000000, ctypes.byref(src), None, 1 << 17, idx, cnt, None, None, 0, None) \
         == T.TRI_ERR_UNSUPPORTED
 
+
+def test_static_scratch_entry_point_validates_like_the_fused_step():
+    import numpy as np
+    from paper_2604_04921_amd import binding as T
+    L = T.lib()
+    assert T.tri_static_scratch_size() == 64 << 20
+    offs = np.array([1, 2, 4], dtype=np.int64)
+    m = T.TriModel(2, 32, 8, 128, 1e6, 0, 3, offs.ctypes.data_as(ctypes.c_void_p), 0)
+    c = T.TriCache()
+    assert L.tri_compress_step_static(ctypes.byref(m), None, ctypes.byref(c), None, 16, None, None, None, None) \
+        == T.TRI_ERR_INVALID_ARG
+    src = _fake_cache(T, n_seqs=64, max_seq_len=65536)   # far more scratch than the array holds
+    assert L.tri_compress_step_static(ctypes.byref(m), 0x60000000, ctypes.byref(src), None, 2048, 0x70000000, 0x70100000,
+                                      None, None) == T.TRI_ERR_WORKSPACE
+    assert b"scratch" in L.tri_last_error()
