@@ -376,6 +376,13 @@ int tri_oracle_gqa_final(const double *raw, int G, int64_t N, double *mu, double
         double m = sum / (double)N;
         double ss = 0.0;
         for (int64_t n = 0; n < N; ++n) ss += (s[n] - m) * (s[n] - m);
+        /* all scores equal: sigma is 0, whatever the rounding of sum / N left in s[n] - m */
+        double lo = s[0], hi = s[0];
+        for (int64_t n = 1; n < N; ++n) {
+            if (s[n] < lo) lo = s[n];
+            if (s[n] > hi) hi = s[n];
+        }
+        if (lo == hi) ss = 0.0;
         mu[g] = m;
         sigma[g] = sqrt(ss / (double)N);
     }

@@ -19,6 +19,7 @@ MUTATIONS = [
     ("norm term dropped", "tri_oracle_s_norm(stats, key, dtype, first, d, pairs);\n        acc += S;",
      "0.0;\n        acc += S;"),
     ("sample sigma", "sigma[g] = sqrt(ss / (double)N);", "sigma[g] = sqrt(ss / (double)(N - 1));"),
+    ("equal scores not recognised", "if (lo == hi) ss = 0.0;", ""),
     ("tie to the higher index", "if (a[j].score > a[i].score) tmp", "if (a[j].score >= a[i].score) tmp"),
     ("min instead of max", "if (g == 0 || z > best) best = z;", "if (g == 0 || z < best) best = z;"),
     ("frequency exponent", "-2.0 * (double)f / (double)d", "-1.0 * (double)f / (double)d"),

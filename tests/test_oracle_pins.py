@@ -230,6 +230,13 @@ def test_zscore_degenerate(oracle):
     np.testing.assert_allclose(final, np.maximum(0.0, z1), rtol=1e-13)
     _, _, f1 = oracle.gqa_final(np.array([[3.0]]))
     assert f1[0] == 0
+    # equal scores whose mean is not exact in binary (3000 x 0.1: sum / N differs from 0.1 in the last bit) still
+    # have sigma = 0: the head contributes 0, not +-1
+    raw = np.vstack([np.full(3000, 0.1), np.linspace(-1.0, 1.0, 3000)])
+    assert np.sum(raw[0]) / 3000 != 0.1
+    mu, sigma, final = oracle.gqa_final(raw)
+    assert sigma[0] == 0
+    np.testing.assert_allclose(final, np.maximum(0.0, (raw[1] - raw[1].mean()) / raw[1].std()), rtol=1e-12, atol=1e-15)
 
 
 def test_head_scale_invariance(oracle):
