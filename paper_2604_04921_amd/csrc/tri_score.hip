@@ -284,8 +284,11 @@ __global__ __launch_bounds__(256) void stats_kernel(StatsArgs a)
             mean = s1 / (double)N;
             double msq = s2 / (double)N;
             double var = msq - mean * mean;
-            // all-equal scores leave only rounding noise here: that head then contributes 0
-            if (var > 1e-14 * msq) rsig = 1.0 / sqrt(var);
+            // Section 4.3 with sigma = 0: the head contributes 0.  The raw scores are fp32 sums of 192 products, so
+            // scores that are equal in exact arithmetic may differ in their last bits here (the same key scored
+            // against two different table bases), and the moments carry that noise: a spread below 3e-6 of the
+            // root mean square is not distinguishable from zero and is read as zero.
+            if (var > 1e-11 * msq) rsig = 1.0 / sqrt(var);
         }
         a.stats[((int64_t)inst * a.G + g) * 2 + 0] = mean;
         a.stats[((int64_t)inst * a.G + g) * 2 + 1] = rsig;

@@ -1,7 +1,10 @@
 """The five benchmark configurations at full size on the GPU, in the launch configuration bench.py times
 (tri_compress_step on a device-generated workload).  The oracle checks a few whole head-instances copied
 back from the device; every head-instance is checked with properties that hold at any size: kept count,
-ascending unique in-range indices, and bit-exact compacted K / V / positions."""
+ascending unique in-range indices, and bit-exact compacted K / V / positions (directly for the contiguous layout,
+through the block table with per-row checksums taken before the step for the paged one).  At these sizes the
+oracle comparison is on the kept sets; raw and final scores are compared element by element in test_gpu_parity.py
+on inputs of up to 16 901 keys."""
 import numpy as np
 import pytest
 import torch
@@ -26,10 +29,20 @@ def instance_from_device(cfg, w, l, s, h):
     return H.to_numpy(k.contiguous()), p.cpu().numpy()
 
 
-def run_full(oracle, cfg, picks, layers=None, positions=None):
+def row_checksums(t, lo, hi):
+    """One int64 per row of t[lo:hi] (last dimension = the row, bf16 or fp32 viewed as 16-bit words): a weighted
+    sum with odd multipliers, enough to tell any two rows of these caches apart.  Done layer by layer to bound
+    the temporaries."""
+    words = t.view(torch.int16)
+    wts = (torch.arange(words.shape[-1], device=t.device, dtype=torch.int64) * 2654435761 + 12345) | 1
+    return torch.stack([(words[l].to(torch.int64) * wts).sum(-1) for l in range(lo, hi)])
+
+
+def run_full(oracle, cfg, picks, layers=None, positions=None, layer0=0):
+    """One fused step on `layers` layers of cfg starting at layer0.  picks: (l, s, h) with l relative to the slab."""
     from paper_2604_04921_amd import binding as T
     L = layers or cfg.n_layers
-    w = device.generate(cfg, positions=positions, layers=L)
+    w = device.generate(cfg, positions=positions, layers=L, layer0=layer0)
     S, Hq, Hkv, B, d, G = cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads, cfg.budget, cfg.head_dim, cfg.group
     dev = "cuda"
     model = T.Model(L, Hq, Hkv, d, cfg.rope_theta, cfg.offsets)
@@ -52,6 +65,9 @@ def run_full(oracle, cfg, picks, layers=None, positions=None):
             n = int(lens[s])
             bt = w["block_table"][s, : -(-n // cfg.block_size)].long()
             v_before[(l, s, h)] = H.to_numpy(w["v"][l, bt, h].reshape(-1, d)[:n].contiguous())
+        # every slot of the pools: checksums of its K row and V row, and its position, before the step
+        ck_before, cv_before = row_checksums(w["k"], 0, L), row_checksums(w["v"], 0, L)   # [L][n_blocks][Hkv][bs]
+        pos_before = w["pos"].clone()
     else:
         kd = torch.zeros((L, S, Hkv, B, d), dtype=w["k"].dtype, device=dev)
         vd = torch.zeros_like(kd)
@@ -71,7 +87,7 @@ def run_full(oracle, cfg, picks, layers=None, positions=None):
     assert bool(((idx < w["seq_len"].view(1, S, 1, 1)) | ~live).all())
     inc = (idx[..., 1:] > idx[..., :-1]) | ~live[..., 1:]
     assert bool(inc.all())
-    # ---- every head-instance, contiguous layout: compacted rows are the selected rows, bit for bit
+    # ---- every head-instance: compacted rows are the selected rows, bit for bit
     if not paged:
         for l in range(L):
             gi = idx[l].clamp(min=0).long()
@@ -82,6 +98,23 @@ def run_full(oracle, cfg, picks, layers=None, positions=None):
                 assert bool(((got == want) | ~m).all())
             wantp = torch.gather(w["pos"][l], 2, gi)
             assert bool(((pd[l] == wantp) | ~live[l]).all())
+    else:
+        # in place through the block table: slot j of (l, s, h) must now hold what slot kept_idx[j] held before
+        # (row checksums of K and V, the position itself), for every head-instance of the slab
+        bs = cfg.block_size
+        btd = w["block_table"].long()                                   # [S][max_blocks]
+        ck_after, cv_after = row_checksums(w["k"], 0, L), row_checksums(w["v"], 0, L)
+        hh = torch.arange(Hkv, device=dev).view(1, Hkv, 1).expand(S, Hkv, B)
+        jj = torch.arange(B, device=dev).view(1, 1, B).expand(S, Hkv, B)
+        dst_blk = torch.gather(btd, 1, (jj[:, 0] // bs).clamp(max=btd.shape[1] - 1)).view(S, 1, B).expand(S, Hkv, B)
+        for l in range(L):
+            n_src = idx[l].clamp(min=0).long()                           # [S][Hkv][B]
+            src_blk = torch.gather(btd.view(S, 1, -1).expand(S, Hkv, -1), 2, n_src // bs)
+            for before, after in ((ck_before, ck_after), (cv_before, cv_after), (pos_before, w["pos"])):
+                want = before[l][src_blk, hh, n_src % bs]
+                got = after[l][dst_blk, hh, jj % bs]
+                assert bool(((got == want) | ~live[l]).all())
+        del ck_before, cv_before, ck_after, cv_after, pos_before
 
     # ---- sampled head-instances against the oracle
     same = 0
@@ -101,10 +134,11 @@ def run_full(oracle, cfg, picks, layers=None, positions=None):
             np.testing.assert_array_equal(k_after, kn[got])
             np.testing.assert_array_equal(v_after, v_before[(l, s, h)][got])
             np.testing.assert_array_equal(p_after, pn[got])
-    print("\n[%s] %d layers, %d head-instances checked by property, %d by the oracle (%d identical index sets)"
-          % (cfg.name, L, L * S * Hkv, len(picks), same), flush=True)
+    print("\n[%s] layers %d..%d, %d head-instances checked by property, %d by the oracle (%d identical index sets)"
+          % (cfg.name, layer0, layer0 + L - 1, L * S * Hkv, len(picks), same), flush=True)
     del w, ws
     torch.cuda.empty_cache()
+    return same
 
 
 def test_c2_layer_full(oracle):
@@ -120,19 +154,26 @@ def test_c3_model_full(oracle, positions):
     run_full(oracle, cfg, [(0, 0, 0), (17, 5, 3), (35, 15, 7)], positions=positions)
 
 
-def test_c4_paged_slab(oracle):
+@pytest.mark.parametrize("slab", [0, 1, 2])
+def test_c4_paged_slabs(oracle, slab):
     """Config 4: ragged paged batch, 64 sequences, block 16, compaction in place.  The full 36 layers need more
-    than the 288 GB of HBM, so the step is run on a slab of 4 layers (head-instances are independent)."""
+    than the 288 GB of HBM, so the step is run as three slabs of 12 layers (head-instances are independent) that
+    together cover every layer.  Six head-instances per slab go through the oracle (shortest and longest
+    sequence among them); every head-instance of every slab is checked through the block table."""
     cfg = recipe.CONFIGS["c4_paged"]
     lens = recipe.seq_lens(cfg)
-    s_short, s_long = int(np.argmin(lens)), int(np.argmax(lens))
-    run_full(oracle, cfg, [(0, s_short, 1), (3, s_long, 6)], layers=4)
+    order = np.argsort(lens)
+    seqs = [int(order[0]), int(order[-1]), int(order[len(order) // 2]), int(order[len(order) // 4]),
+            int(order[3 * len(order) // 4]), int(order[1])]
+    picks = [((5 * i + 2 * slab) % 12, seqs[(i + slab) % 6], (3 * i + slab) % 8) for i in range(6)]
+    run_full(oracle, cfg, picks, layers=12, layer0=12 * slab)
 
 
 def test_c5_long(oracle):
-    """Config 5: 64 layers, G = 8, N = 131072, B = 4096, 32 offsets (up to 2^31), 5 % x10 outliers."""
+    """Config 5: 64 layers, G = 8, N = 131072, B = 4096, 32 offsets (up to 2^31), 5 % x10 outliers: eight
+    head-instances spread over the layers and KV heads go through the oracle."""
     cfg = recipe.CONFIGS["c5_long"]
-    run_full(oracle, cfg, [(41, 0, 5)])
+    run_full(oracle, cfg, [(9 * i, 0, (5 * i + 3) % 8) for i in range(8)])
 
 
 def test_steady_state_ordered(oracle):

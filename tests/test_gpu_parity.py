@@ -218,25 +218,96 @@ def test_sequence_lengths_outside_the_host_bound_are_clamped():
     assert outs[0][2].tolist() == [100, 0]
 
 
-def test_fused_step_agrees_with_the_three_calls():
+@pytest.mark.parametrize("seq_len,min_len,budget,ties", [(5000, 900, 333, False), (40000, 20000, 2048, False),
+                                                         (70000, 33000, 3000, False), (40000, 20000, 2048, True),
+                                                         (70000, 33000, 3000, True)])
+def test_fused_step_agrees_with_the_three_calls(seq_len, min_len, budget, ties):
     """tri_compress_step forms the final scores inside the selection; tri_score writes them out for tri_select_topk.
-    Both go through the same z-score arithmetic, so the kept sets are identical, not merely within the tie band."""
-    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=2, n_seqs=3, n_q_heads=8, n_kv_heads=2, seq_len=5000,
-                        min_seq_len=900, budget=333, n_calib=128)
+    Both go through the same z-score arithmetic, so the kept sets are identical, not merely within the tie band.
+    Beyond 32768 keys the fused selection keeps its integer keys in LDS (sequences up to 32768 keys) or in the
+    workspace (longer ones); the ragged lengths here exercise both.  ties: stretches of the cache hold copies of one
+    key at one position, i.e. hundreds of equal final scores, some of them around the budget's threshold."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1 if seq_len > 5000 else 2, n_seqs=3, n_q_heads=8,
+                        n_kv_heads=2, seq_len=seq_len, min_seq_len=min_len, budget=budget, n_calib=128)
     w = recipe.generate(cfg)
+    if ties:
+        for start, count in ((1000, 700), (9000, 1500), (15000, 2600)):
+            w["k"][..., start:start + count, :] = w["k"][..., start - 1:start, :]
+            w["pos"][..., start:start + count] = w["pos"][..., start - 1:start]
     run = H.GpuRun(cfg, w)
     run.build_centers()
-    run.score()
+    final, _ = run.score(want_raw=False)
     idx_a, cnt_a = run.select()
+    if ties:   # most copies tie bit for bit (a wave that scores them against another table base may differ in the
+        # last bit); count the head-instances whose threshold falls among equal scores
+        stretch = final[0, 0, 0, 1000:1700]
+        assert np.mean(stretch == np.median(stretch)) > 0.5
+        at_threshold = 0
+        for l in range(cfg.n_layers):
+            for s_ in range(cfg.n_seqs):
+                for h in range(cfg.n_kv_heads):
+                    n = int(w["seq_len"][s_])
+                    f = np.sort(final[l, s_, h, :n])[::-1]
+                    at_threshold += int(f[budget - 1] == f[budget])
+        print("\n[ties] head-instances whose threshold lies among equal scores: %d" % at_threshold)
     run.kept_idx.fill_(-1)
     run.kept_cnt.fill_(-1)
-    kd, vd, pd = torch.zeros_like(run.k), torch.zeros_like(run.v), torch.zeros_like(run.pos)
-    dst = run.B.Cache(kd, vd, pd, run.seq_len, run.cur_pos, run.nmax)
+    kd = torch.zeros((cfg.n_layers, cfg.n_seqs, cfg.n_kv_heads, budget, cfg.head_dim), dtype=run.k.dtype, device="cuda")
+    vd, pd = torch.zeros_like(kd), torch.zeros(kd.shape[:-1], dtype=torch.int32, device="cuda")
+    dst = run.B.Cache(kd, vd, pd, run.seq_len, run.cur_pos, budget)
     run.B.tri_compress_step(run.model, run.centers, run.cache, dst, cfg.budget, run.kept_idx, run.kept_cnt,
                             run.new_len, run.ws)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(run.kept_cnt.cpu().numpy(), cnt_a)
     np.testing.assert_array_equal(run.kept_idx.cpu().numpy(), idx_a)
+    # and the selection itself is the oracle's on the same fp32 scores (ties to the lower slot)
+    from oracle import tri_oracle as O
+    for s_ in range(cfg.n_seqs):
+        n = int(w["seq_len"][s_])
+        ref = O.topk(final[0, s_, 1, :n].astype(np.float64), budget)
+        np.testing.assert_array_equal(idx_a[0, s_, 1, :len(ref)], ref)
+
+
+def test_head_without_statistics_and_constant_scores(oracle):
+    """Section 4.3 with sigma = 0 (a head whose scores are all equal contributes 0 to the maximum).
+    (a) One query head of each group has an all-zero statistics row: its raw scores are exactly 0 on both sides and
+    it drops out of the maximum.  (b) A head-instance whose keys are all copies of one key at one position: every
+    head's scores are constant, every final score is 0, and the budget goes to the lowest slots."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=2, n_q_heads=8, n_kv_heads=2, seq_len=3000,
+                        min_seq_len=3000, budget=500, n_calib=128)
+    w = recipe.generate(cfg)
+    # (b): sequence 1, KV head 1
+    w["k"][0, 1, 1, :, :] = w["k"][0, 1, 1, 77:78, :]
+    w["pos"][0, 1, 1, :] = w["pos"][0, 1, 1, 77]
+    run = H.GpuRun(cfg, w)
+    run.build_centers()
+    stats = oracle.centers(w["q_samples"])
+    stats[0, 2] = 0.0      # (a): query head 2 of KV head 0 and query head 5 of KV head 1
+    stats[0, 5] = 0.0
+    run.centers.copy_(torch.from_numpy(stats))
+    final, raw = run.score()
+    idx, cnt = run.select()
+    G = cfg.group
+    assert np.all(raw[0, :, 2, :] == 0.0) and np.all(raw[0, :, 5, :] == 0.0)
+    for s_ in range(cfg.n_seqs):
+        for h in range(cfg.n_kv_heads):
+            n = int(w["seq_len"][s_])
+            ref = oracle_instance(oracle, cfg, w, stats, 0, s_, h)
+            live = [g for g in range(G) if h * G + g not in (2, 5)]
+            if (s_, h) == (1, 1):
+                assert np.all(ref["final"] == 0.0) and np.all(final[0, s_, h, :n] == 0.0)
+                np.testing.assert_array_equal(idx[0, s_, h, :cfg.budget], np.arange(cfg.budget))
+                np.testing.assert_array_equal(ref["idx"], np.arange(cfg.budget))
+                continue
+            H.check_raw(raw[0, s_, h * G:(h + 1) * G, :n][live], ref["raw"][live])
+            H.check_final(final[0, s_, h, :n], ref["final"])
+            H.check_kept(idx[0, s_, h], int(cnt[0, s_, h]), ref["final"], ref["idx"], n, cfg.budget)
+    # the fused step takes the same decisions
+    run.kept_idx.fill_(-1)
+    run.B.tri_compress_step(run.model, run.centers, run.cache, run.cache, cfg.budget, run.kept_idx, run.kept_cnt,
+                            run.new_len, run.ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(run.kept_idx.cpu().numpy(), idx)
 
 
 @pytest.mark.parametrize("kind", ["linear17", "geometric13", "single", "sixty_four"])

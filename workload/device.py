@@ -70,23 +70,27 @@ def fill_normal(out, seed, tag):
     assert rc == 0
 
 
-def generate(cfg, positions=None, layers=None):
+def generate(cfg, positions=None, layers=None, layer0=0):
     """The workload of `cfg` on cuda:0 as torch tensors.
 
     positions overrides cfg.positions ("dense"; "sparse" / "sparse16": sorted unique draws from [0, 2N) / [0, 16N);
     "scattered": the draws of "sparse16" left in random slot order); layers overrides cfg.n_layers (layer slabs
-    for configurations that do not fit in HBM at once).  Returns a dict with q_samples, k, v, pos,
+    for configurations that do not fit in HBM at once) and layer0 is the slab's first layer: the slab holds layers
+    layer0 .. layer0 + layers - 1 of the configuration, each with its own centres and noise).  Returns a dict with q_samples, k, v, pos,
     seq_len, cur_pos and, for paged configurations, block_table (k, v, pos are then block pools)."""
     L = cfg.n_layers if layers is None else layers
     S, Hq, Hkv, F, N = cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads, cfg.n_bands, cfg.seq_len
     dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     mode = positions or cfg.positions
-    qc = recipe.draw_centres(recipe._rng(cfg.seed, 1), (cfg.n_layers, Hq), F)[:L]
-    kc = recipe.draw_centres(recipe._rng(cfg.seed, 2), (cfg.n_layers, Hkv), F)[:L]
+    assert 0 <= layer0 and layer0 + L <= max(cfg.n_layers, L)
+    qc = recipe.draw_centres(recipe._rng(cfg.seed, 1), (max(cfg.n_layers, layer0 + L), Hq), F)[layer0:layer0 + L]
+    kc = recipe.draw_centres(recipe._rng(cfg.seed, 2), (max(cfg.n_layers, layer0 + L), Hkv), F)[layer0:layer0 + L]
+    tag0 = 1000 * layer0   # a slab's noise differs from the other slabs'
+
     qc_t, kc_t = _centres_tensor(qc.reshape(-1, F)), _centres_tensor(kc.reshape(-1, F))
     out = {}
     q = torch.empty((cfg.n_calib, L, Hq, 2 * F), dtype=dt, device="cuda")
-    fill_samples(q, qc_t, cfg.n_calib, L * Hq, 1, cfg.noise, 0.0, 1.0, cfg.seed, 3)
+    fill_samples(q, qc_t, cfg.n_calib, L * Hq, 1, cfg.noise, 0.0, 1.0, cfg.seed, 3 + tag0)
     out["q_samples"] = q
     lens = recipe.seq_lens(cfg)
     out["seq_len"] = torch.from_numpy(lens).cuda()
@@ -98,9 +102,9 @@ def generate(cfg, positions=None, layers=None):
         bt, nb = recipe.paged_layout(cfg, lens)
         out["block_table"] = torch.from_numpy(bt).cuda()
         k = torch.empty((L, nb, Hkv, bs, 2 * F), dtype=dt, device="cuda")
-        fill_samples(k, kc_t, nb, Hkv, bs, cfg.noise, cfg.outlier_p, cfg.outlier_scale, cfg.seed, 4)
+        fill_samples(k, kc_t, nb, Hkv, bs, cfg.noise, cfg.outlier_p, cfg.outlier_scale, cfg.seed, 4 + tag0)
         v = torch.empty_like(k)
-        fill_normal(v, cfg.seed, 5)
+        fill_normal(v, cfg.seed, 5 + tag0)
         # slot n of sequence s holds position n: scatter the arange through the block table
         pos = torch.zeros((L, nb, Hkv, bs), dtype=torch.int32, device="cuda")
         btd = out["block_table"]
@@ -111,9 +115,9 @@ def generate(cfg, positions=None, layers=None):
         assert mode == "dense"
     else:
         k = torch.empty((L, S, Hkv, N, 2 * F), dtype=dt, device="cuda")
-        fill_samples(k, kc_t, S, Hkv, N, cfg.noise, cfg.outlier_p, cfg.outlier_scale, cfg.seed, 4)
+        fill_samples(k, kc_t, S, Hkv, N, cfg.noise, cfg.outlier_p, cfg.outlier_scale, cfg.seed, 4 + tag0)
         v = torch.empty_like(k)
-        fill_normal(v, cfg.seed, 5)
+        fill_normal(v, cfg.seed, 5 + tag0)
         if mode == "dense":
             pos = torch.arange(N, dtype=torch.int32, device="cuda").expand(L, S, Hkv, N).contiguous()
         else:
