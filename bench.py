@@ -21,8 +21,20 @@ STEP_BYTES = lambda n, b: 260 * n + 1032 * min(n, b)   # + survivors' K, V, pos 
 
 # HBM bytes of one score-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE in two runs,
 # each scaled by what the same counter reads for a plain device copy of known size: FETCH_SIZE reads 0.5 of the
-# bytes a 1 GiB copy fetches, WRITE_SIZE 1.0); summary in profiles/pmc_traffic_c3_model.md.
-MEASURED_TRAFFIC = {"c3_model/dense": 39.80e9 + 2.43e9}
+# bytes a 1 GiB copy fetches, WRITE_SIZE 1.0); summary in profiles/pmc_traffic_c3_model.md.  The figure belongs to
+# the kernel sources it was measured on: it is reported only while their hash (kernel_sources_sha16) is unchanged.
+MEASURED_TRAFFIC = {"c3_model/dense": {"bytes": 39.80e9 + 2.43e9, "sources_sha16": "unmeasured"}}
+
+
+def kernel_sources_sha16():
+    """Hash of the library's kernel sources (csrc/*.hip, *.h, sorted by name)."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2604_04921_amd", "csrc", "*.h*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
 
 
 def main():
@@ -42,6 +54,11 @@ def main():
     ap.add_argument("--post-rope", action="store_true", help="treat the cache as holding post-RoPE keys (k_rotated)")
     ap.add_argument("--half-split", action="store_true", help="band f = (x[f], x[f + d/2]) instead of (x[2f], x[2f+1])")
     ap.add_argument("--variant", type=int, default=0, help="score variant (0 full, 1 trig only, 2 norm only, 3 un-weighted norm)")
+    ap.add_argument("--resident", action="store_true",
+                    help="measurement aid: every head-instance reads the K rows of the first one (strides 0), so the "
+                         "score kernel runs out of the caches instead of HBM; not the benchmark")
+    ap.add_argument("--inst-probe", action="store_true",
+                    help="instead of the benchmark, print the issue rates of the instructions the score kernel is made of")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic for scaling rocprofv3 byte counters)")
     ap.add_argument("--hbm-probe", action="store_true",
@@ -51,6 +68,10 @@ def main():
     if args.hbm_probe:
         from workload import device
         print(json.dumps({"hbm_probe_GBps": device.hbm_probe(), "peak_GBps": HBM_PEAK_GBS}), flush=True)
+        return
+    if args.inst_probe:
+        from workload import device
+        sys.stdout.write(device.inst_probe())
         return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
@@ -62,6 +83,8 @@ def main():
     from paper_2604_04921_amd import binding as T
     from workload import device, recipe
 
+    if args.resident:
+        args.no_cpu = True   # the head-instances no longer hold their own keys
     cfg = recipe.CONFIGS[args.config]
     if args.seqs:
         cfg = recipe.scaled(cfg, n_seqs=args.seqs)
@@ -72,7 +95,12 @@ def main():
     w = device.generate(cfg, positions=mode, layers=L)
     S, Hq, Hkv, B, d = cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads, cfg.budget, cfg.head_dim
     model = T.Model(L, Hq, Hkv, d, cfg.rope_theta, cfg.offsets, pairs=int(args.half_split), score_variant=args.variant)
-    src = T.Cache(w["k"], w["v"], w["pos"], w["seq_len"], w["cur_pos"], cfg.seq_len, w.get("block_table"),
+    k_view, v_view = w["k"], w["v"]
+    if args.resident:   # one head-instance's rows for everybody: a cache-resident read stream
+        assert "block_table" not in w and not args.fill, "--resident: contiguous layout, out-of-place compaction"
+        k_view = w["k"][:1, :1, :1].expand(L, cfg.n_seqs, cfg.n_kv_heads, cfg.seq_len, cfg.head_dim)
+        v_view = w["v"][:1, :1, :1].expand(L, cfg.n_seqs, cfg.n_kv_heads, cfg.seq_len, cfg.head_dim)
+    src = T.Cache(k_view, v_view, w["pos"], w["seq_len"], w["cur_pos"], cfg.seq_len, w.get("block_table"),
                   k_rotated=args.post_rope)
     centers = torch.empty((L, Hq, d // 2, 3), dtype=torch.float32, device=dev)
     T.tri_build_centers(model, w["q_samples"], centers)
@@ -110,6 +138,20 @@ def main():
         else:
             T.tri_compress_step(model, centers, src, dst, B, kept_idx, kept_cnt, new_len, ws)
 
+    # In-place modes (paged: dst is src; --fill) overwrite the cache they score.  Every step must see the configured
+    # workload, so the cache is put back from a device copy before each step, outside the timed region, and the
+    # steps are timed one by one; the out-of-place default times all steps in one bracket.
+    in_place = dst is None or dst is src
+    orig = {n: w[n].clone() for n in ("k", "v", "pos")} if in_place else None
+
+    def restore():
+        if in_place:
+            for n in ("k", "v", "pos"):
+                w[n].copy_(orig[n])
+
+    # the CPU oracle's sample is taken from the untouched cache
+    cpu_sample = None if args.no_cpu else cpu_sample_inputs(cfg, w, L, args.cpu_instances, paged)
+
     # how many score-kernel launches one step makes (the hook brackets each of them)
     probe = [torch.cuda.Event(enable_timing=True) for _ in range(2 * 256)]
     for e in probe:
@@ -120,6 +162,7 @@ def main():
     launches = T.tri_timing_detach()
     torch.cuda.synchronize()
     for _ in range(max(0, args.warmup - 1)):
+        restore()
         step()
     torch.cuda.synchronize()
 
@@ -128,18 +171,28 @@ def main():
         e.record()
     torch.cuda.synchronize()
     keep = T.tri_timing_attach(events)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if in_place:
+        elapsed = 0.0
+        for _ in range(args.steps):
+            restore()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            step()
+            torch.cuda.synchronize()
+            elapsed += time.perf_counter() - t0
+    else:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     got = T.tri_timing_detach()
     assert got == launches * args.steps, (got, launches, args.steps)
     del keep
 
     lens = w["seq_len"].cpu().numpy().astype(np.int64)
     keys = int(lens.sum()) * L * Hkv
-    ms = (t1 - t0) * 1e3 / args.steps
+    ms = elapsed * 1e3 / args.steps
     value = keys / (ms * 1e-3) / 1e9
     k_ms = [events[2 * i].elapsed_time(events[2 * i + 1]) for i in range(launches * args.steps)]
     launch_ms = float(np.mean(k_ms))
@@ -153,7 +206,7 @@ def main():
     mfma_path = eb == 2 and (cfg.block_size == 0 or cfg.block_size >= 16)   # which of the two score kernels ran
     roofline = {"bound": "hbm", "kernel": "score_mfma_kernel" if mfma_path else "score_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get("%s/%s" % (cfg.name, mode)),
+                "traffic": measured_traffic(cfg.name, mode, args),
                 "launch_ms": round(launch_ms, 4), "launches_per_step": launches,
                 "algorithmic_bytes_per_launch": int(bytes_per_launch)}
     if step_bytes:
@@ -162,8 +215,7 @@ def main():
 
     cpu = None
     if not args.no_cpu:
-        cpu = cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, args.cpu_instances, paged, args.variant, args.post_rope,
-                           int(args.half_split))
+        cpu = cpu_baseline(cfg, cpu_sample, centers, kept_idx, kept_cnt, args.variant, args.post_rope, int(args.half_split))
 
     out = {"metric": "cached keys scored+selected+compacted per second", "value": round(value, 3), "unit": "Gkeys/s",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
@@ -175,25 +227,32 @@ def main():
                       "keys": keys, "entry": "split" if args.split else "tri_compress_step",
                       "compaction": "fill" if args.fill else "ordered",
                       "keys_stored": "post-rope" if args.post_rope else "pre-rope", "score_variant": args.variant, "pairs": "half-split" if args.half_split else "interleaved",
+                      "timed": "each step alone, cache restored before it" if in_place else "all steps in one bracket",
+                      "resident": bool(args.resident), "kernel_sources_sha16": kernel_sources_sha16(),
                       "generate_s": round(t_gen, 1)},
            "roofline": roofline, "cpu_baseline": cpu}
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, n_inst, paged, variant=0, rotated=False, pairs=0):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: whole head-instances spread
-    over layers and sequences, copied back from the device.  Also confirms the GPU's kept sets on them."""
+def measured_traffic(name, mode, args):
+    """The counter-measured HBM bytes of one score launch, if they were measured on these kernel sources and this
+    is the plain workload they were measured on; else None."""
+    m = MEASURED_TRAFFIC.get("%s/%s" % (name, mode))
+    plain = not (args.resident or args.post_rope or args.half_split or args.variant or args.seqs or args.layers)
+    if m is None or not plain or m["sources_sha16"] != kernel_sources_sha16():
+        return None
+    return m["bytes"]
+
+
+def cpu_sample_inputs(cfg, w, L, n_inst, paged):
+    """Whole head-instances spread over layers and sequences, copied back from the device (before any step
+    touches the cache): [(l, s, h), K rows, positions, cur_pos]."""
     import numpy as np
     import torch
-    from oracle import tri_oracle as O
-    from workload import recipe
-
-    S, Hkv, G = cfg.n_seqs, cfg.n_kv_heads, cfg.group
-    stats = centers.cpu().numpy()
+    S, Hkv = cfg.n_seqs, cfg.n_kv_heads
     lens = w["seq_len"].cpu().numpy()
     cur = w["cur_pos"].cpu().numpy()
     picks = [((i * (L - 1)) // max(1, n_inst - 1) if n_inst > 1 else 0, (i * 5) % S, (i * 3) % Hkv) for i in range(n_inst)]
-    threads = min(16, os.cpu_count() or 1)
     jobs = []
     for (l, s, h) in picks:
         n = int(lens[s])
@@ -205,16 +264,28 @@ def cpu_baseline(cfg, w, L, centers, kept_idx, kept_cnt, n_inst, paged, variant=
         else:
             k, p = w["k"][l, s, h, :n], w["pos"][l, s, h, :n]
         kn = k.contiguous().view(torch.int16).cpu().numpy().view(np.uint16) if k.dtype == torch.bfloat16 else k.cpu().numpy()
-        jobs.append((stats[l, h * G:(h + 1) * G], kn, p.cpu().numpy(), int(cur[s])))
+        jobs.append(((l, s, h), kn, p.cpu().numpy(), int(cur[s])))
+    return jobs
+
+
+def cpu_baseline(cfg, jobs, centers, kept_idx, kept_cnt, variant=0, rotated=False, pairs=0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: whole head-instances spread
+    over layers and sequences.  Also confirms the GPU's kept sets on them."""
+    import numpy as np
+    from oracle import tri_oracle as O
+
+    G = cfg.group
+    stats = centers.cpu().numpy()
+    threads = min(16, os.cpu_count() or 1)
     O.lib()
     t0 = time.perf_counter()
-    res = [O.head_instance(st, kn, p, c, cfg.rope_theta, cfg.offsets, cfg.budget, threads=threads, variant=variant,
-                            rotated=rotated, pairs=pairs)
-           for (st, kn, p, c) in jobs]
+    res = [O.head_instance(stats[l, h * G:(h + 1) * G], kn, p, c, cfg.rope_theta, cfg.offsets, cfg.budget, threads=threads,
+                            variant=variant, rotated=rotated, pairs=pairs)
+           for ((l, s, h), kn, p, c) in jobs]
     dt = time.perf_counter() - t0
     nkeys = sum(j[1].shape[0] for j in jobs)
     same = 0
-    for (l, s, h), r in zip(picks, res):
+    for ((l, s, h), _, _, _), r in zip(jobs, res):
         c = int(kept_cnt[l, s, h])
         same += int(np.array_equal(kept_idx[l, s, h, :c].cpu().numpy(), r["idx"]))
     return {"value": round(nkeys / dt / 1e9, 9), "unit": "Gkeys/s", "cores": threads, "kind": "oracle",

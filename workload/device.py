@@ -17,13 +17,30 @@ _SRC = os.path.join(_HERE, "gen.hip")
 LIB_PATH = os.path.join(_HERE, "libtri_workload.so")
 
 
+PROBE_SRC = os.path.join(_HERE, "inst_probe.hip")
+PROBE_PATH = os.path.join(_HERE, "inst_probe")
+
+
 def build(verbose=False):
-    cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-shared", _SRC, "-o", LIB_PATH]
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    """The generator's library and the instruction-rate probe (a stand-alone program)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = ["--offload-arch=gfx950", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+    for cmd in ([hipcc, *flags, "-O3", "-fPIC", "-shared", _SRC, "-o", LIB_PATH],
+                [hipcc, *flags, "-O2", PROBE_SRC, "-o", PROBE_PATH]):
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stdout)
     return LIB_PATH
+
+
+def inst_probe():
+    """Runs the instruction-rate probe on the current GPU (as a child process) and returns its table."""
+    if not os.path.exists(PROBE_PATH):
+        raise RuntimeError("workload/inst_probe is not built (workload.device.build())")
+    res = subprocess.run([PROBE_PATH], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300)
+    if res.returncode != 0:
+        raise RuntimeError("inst_probe failed:\n" + res.stdout)
+    return res.stdout
 
 
 _lib = None
