@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtri.so")
-SOURCES = ["tri_api.hip", "tri_centers.hip", "tri_score.hip", "tri_score_mfma.hip", "tri_select.hip", "tri_compact.hip"]
+SOURCES = ["tri_api.hip", "tri_centers.hip", "tri_score.hip", "tri_score_mfma.hip", "tri_score_lane.hip", "tri_select.hip", "tri_compact.hip"]
 
 # packed fp32 VALU forms are switched off for every kernel of this library
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

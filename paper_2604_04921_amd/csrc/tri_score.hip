@@ -376,11 +376,19 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
     const int tile_keys = fast ? kFastChunk : kScoreTile;
     sa.n_tiles = (c.max_seq_len + tile_keys - 1) / tile_keys;
     tri_status rc = TRI_OK;
-    if (fast && (rc = launch_phasor_table(m.rope_theta, const_cast<uint4 *>(sa.phasors), st)) != TRI_OK) return rc;
+    // interleaved pairs: one key per lane; half-split pairs: the kernel that spreads a key over sixteen lanes
+    const bool lane_kernel = fast && m.pairs == TRI_PAIR_INTERLEAVED;
+    if (fast && !c.k_rotated) {
+        rc = lane_kernel ? launch_lane_phasor_table(m.rope_theta, const_cast<uint4 *>(sa.phasors), st)
+                         : launch_phasor_table(m.rope_theta, const_cast<uint4 *>(sa.phasors), st);
+        if (rc != TRI_OK) return rc;
+    }
     hipEvent_t ev0, ev1;
     const bool timed = timing_next(&ev0, &ev1);
     if (timed) (void)hipEventRecord(ev0, st);
-    if (fast) {
+    if (lane_kernel) {
+        rc = launch_score_lane(G, sa, st);
+    } else if (fast) {
         rc = launch_score_fast(G, sa, m.pairs == TRI_PAIR_HALF, st);
     } else {
         dim3 grid(sa.n_tiles, c.n_seqs * m.n_kv_heads, m.n_layers);

@@ -62,6 +62,9 @@ __device__ __forceinline__ void build_work_list(const int32_t *seq_len, int n_se
 tri_status launch_phasor_table(double theta, uint4 *phasors, hipStream_t st);
 // bf16 keys; G in 1..8
 tri_status launch_score_fast(int G, const ScoreArgs &sa, bool half_split, hipStream_t st);
+// bf16 keys with interleaved pairs, one key per lane (tri_score_lane.hip); its own phasor table layout
+tri_status launch_lane_phasor_table(double theta, uint4 *phasors, hipStream_t st);
+tri_status launch_score_lane(int G, const ScoreArgs &sa, hipStream_t st);
 // ints the MFMA kernel's work list takes: a header and one (sequence, chunk) pair per possible chunk
 inline size_t fast_work_ints(int64_t n_seqs, int64_t max_seq_len)
 {
