@@ -236,7 +236,7 @@ double tri_oracle_score_avg(const float *stats, const void *key, int dtype, int6
 /*
  * All raw scores of one head-instance (one sequence, layer and KV head): the
  * averaged score of every cached key under each of the G query heads of the
- * group (Section 4.3, "each key receives G different scores").
+ * group (Section 4.3: one score per query head of the group for every key).
  *   stats  [G][F][3]     K  N rows of d elements, row n at element n*row_stride
  *   pos    [N] int32     raw [G][N] double
  */
@@ -397,7 +397,7 @@ int tri_oracle_gqa_final(const double *raw, int G, int64_t N, double *mu, double
     return 0;
 }
 
-/* ---- top-B: a full stable sort (Section 4.3, "retain the top-B keys") ---- */
+/* ---- top-B: a full stable sort (Section 4.3: the B keys with the largest final score stay) ---- */
 
 typedef struct {
     double score;
@@ -458,7 +458,7 @@ int tri_oracle_topk(const double *final, int64_t N, int64_t B, int32_t *idx, int
 }
 
 /*
- * Eviction as a compaction (Section 4.3, "evict the rest"): row j of the
+ * Eviction as a compaction (Section 4.3: every other key leaves the cache): row j of the
  * result is row idx[j] of the source.  idx ascending, so idx[j] >= j and the
  * ascending loop is also correct when dst and src are the same buffer.
  */
