@@ -390,7 +390,7 @@ tri_status tri_score(const tri_model *model, const float *centers, const tri_cac
     if ((rc = check_limits(*model, *cache, 0, "tri_score")) != TRI_OK) return rc;
     const Workspace wl = workspace_layout(*model, *cache, 1);
     if ((rc = check_workspace(wl, workspace, ws_bytes)) != TRI_OK) return rc;
-    return launch_score(*model, centers, *cache, final_out, raw_out, (char *)workspace, wl, (hipStream_t)stream);
+    return launch_score(*model, centers, *cache, final_out, raw_out, (char *)workspace, wl, nullptr, (hipStream_t)stream);
 }
 
 tri_status tri_select_topk(const tri_model *model, const float *final_scores, const tri_cache *cache,
@@ -410,7 +410,8 @@ tri_status tri_select_topk(const tri_model *model, const float *final_scores, co
         return TRI_ERR_INVALID_ARG;
     }
     if ((rc = check_limits(*model, *cache, budget, "tri_select_topk")) != TRI_OK) return rc;
-    return launch_select(*model, final_scores, nullptr, nullptr, nullptr, *cache, budget, kept_idx, kept_cnt,
+    return launch_select(*model, final_scores, nullptr, nullptr, nullptr, MomentLayout{1, 1}, nullptr, *cache, budget,
+                         kept_idx, kept_cnt,
                          (hipStream_t)stream);
 }
 
@@ -467,10 +468,12 @@ static tri_status run_step(const tri_model *model, const float *centers, const t
                            const Workspace &wl, void *stream)
 {
     tri_status rc;
-    // raw scores and their statistics stay in the workspace; the selection forms the final scores itself
-    if ((rc = launch_score(*model, centers, *src, nullptr, nullptr, ws, wl, (hipStream_t)stream)) != TRI_OK) return rc;
-    if ((rc = launch_select(*model, nullptr, reinterpret_cast<const float *>(ws + wl.raw),
-                            reinterpret_cast<const double *>(ws + wl.stats),
+    // raw scores and their moments stay in the workspace; the selection forms statistics and final scores itself
+    MomentLayout moments{1, 1};
+    if ((rc = launch_score(*model, centers, *src, nullptr, nullptr, ws, wl, &moments, (hipStream_t)stream)) != TRI_OK)
+        return rc;
+    if ((rc = launch_select(*model, nullptr, reinterpret_cast<const float *>(ws + wl.raw), nullptr,
+                            reinterpret_cast<const double *>(ws + wl.partials), moments,
                             reinterpret_cast<uint32_t *>(ws + wl.final_), *src, budget, kept_idx, kept_cnt,
                             (hipStream_t)stream)) != TRI_OK)
         return rc;

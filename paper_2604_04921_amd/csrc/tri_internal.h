@@ -58,6 +58,37 @@ __device__ __forceinline__ ZParams z_params(double mu, double inv_sigma)
 }
 __device__ __forceinline__ float z_score(float raw, const ZParams &p) { return ((raw - p.mu_hi) - p.mu_lo) * p.rs; }
 
+// Section 4.3, mu_g and 1/sigma_g of one query head from the per-tile sums of its raw scores and of their squares.
+// `col` points at the head's entry of the head-instance's first tile, entries of successive tiles lie `stride`
+// doubles apart.  The tiles are added in sixteen interleaved groups and the groups in order: stats_kernel (one thread
+// per group) and the selection kernels (one thread per head) both call this, so both get the same bits.
+__device__ __forceinline__ double tile_sum(const double *col, int tiles, int stride)
+{
+    double tot = 0.0;
+    for (int k = 0; k < 16; ++k) {
+        double acc = 0.0;
+        for (int t = k; t < tiles; t += 16) acc += col[(int64_t)t * stride];
+        tot += acc;
+    }
+    return tot;
+}
+__device__ __forceinline__ void moments_to_stats(double s1, double s2, int N, double *mean_out, double *rsig_out)
+{
+    double mean = 0.0, rsig = 0.0;
+    if (N > 0) {
+        mean = s1 / (double)N;
+        const double msq = s2 / (double)N;
+        const double var = msq - mean * mean;
+        // sigma = 0: the head contributes 0.  The raw scores are fp32 sums of 192 products, so scores that are equal
+        // in exact arithmetic may differ in their last bits (the same key scored against two different table
+        // bases), and the moments carry that noise: a spread below 3e-6 of the root mean square is not
+        // distinguishable from zero and is read as zero.
+        if (var > 1e-11 * msq) rsig = 1.0 / sqrt(var);
+    }
+    *mean_out = mean;
+    *rsig_out = rsig;
+}
+
 // Element offset of slot n of (layer, seq, head) in k / v.
 // The slot stride is below 2^31 (checked on the host) and n >= 0, so the per-lane product is one 32 x 32 -> 64
 // bit multiply; everything else is uniform over a workgroup and stays in scalar registers.
@@ -114,12 +145,19 @@ tri_status launch_centers_finalize(const tri_model &m, const double *sums, int64
                                    hipStream_t st);
 tri_status launch_diagnostics(const tri_model &m, const float *q_centers, const float *k_centers, float *mrl,
                               float *contrib, int32_t top_k, int32_t *top, hipStream_t st);
+// final_out == NULL (fused step): the moments stay in the workspace's `partials` (layout returned through
+// moments) and no statistics are formed here: the selection does that itself.
+struct MomentLayout {
+    int32_t n_tiles;     // entries per head-instance
+    int32_t tile_keys;   // keys per entry
+};
 tri_status launch_score(const tri_model &m, const float *centers, const tri_cache &c, float *final_out,
-                        float *raw_out, char *ws, const Workspace &wl, hipStream_t st);
-// final_scores given: select on them; else form them from raw + stats (scratch: keys of long sequences)
+                        float *raw_out, char *ws, const Workspace &wl, MomentLayout *moments, hipStream_t st);
+// final_scores given: select on them; else form them from the raw scores and either stats (mean, 1/sigma) or, when
+// partials is given, the per-tile moments (scratch: keys of long sequences)
 tri_status launch_select(const tri_model &m, const float *final_scores, const float *raw, const double *stats,
-                         uint32_t *scratch, const tri_cache &c, int32_t budget, int32_t *kept_idx,
-                         int32_t *kept_cnt, hipStream_t st);
+                         const double *partials, MomentLayout moments, uint32_t *scratch, const tri_cache &c,
+                         int32_t budget, int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st);
 tri_status launch_compact(const tri_model &m, const tri_cache &src, const tri_cache &dst, int32_t budget,
                           const int32_t *kept_idx, const int32_t *kept_cnt, int32_t *new_seq_len,
                           hipStream_t st);

@@ -9,6 +9,8 @@
 // The fold kernel builds (Re Qhat, Im Qhat, c) per (layer, sequence, query head, band) in double;
 // the score kernel then needs, per key and band, one rotation of the key by its own position,
 // one modulus, and three FMAs per query head -- independent of |D|.
+#include <atomic>
+
 #include "tri_score_common.h"
 
 namespace tri {
@@ -25,6 +27,8 @@ struct FoldArgs {
     const int32_t *cur_pos; // [S]
     const int32_t *seq_len; // [S]
     int32_t *work;          // work list of the MFMA score kernel, or NULL when the generic kernel runs
+    int32_t chunk_keys;     // keys per entry of that list
+    float4 *lane_table;     // relative-position phasor table of the one-key-per-lane kernel to fill in, or NULL
     int32_t max_seq_len;
     int32_t S, Hq, Hkv, G;
     double theta;
@@ -43,12 +47,17 @@ __device__ __forceinline__ void unit_phasor(double t, double rev, double *c, dou
 
 // The phasors the fold needs depend on the band and, for the query position, on the sequence only: they
 // are evaluated once here (double-precision pow / sincos are long software routines) instead of once per
-// query head and layer.  grid (2 + S), block F: thread = band.  The last workgroup has nothing to do with phasors:
-// it lists the chunks of the MFMA score kernel (a launch of its own would cost more than the list).
+// query head and layer.  grid (2 + S), block F: thread = band.  Workgroup S + 1 has nothing to do with phasors:
+// it lists the chunks of the MFMA score kernel (a launch of its own would cost more than the list); nor have the
+// kLaneTableEntries / F workgroups after it, which fill the one-key-per-lane kernel's table when it is asked for.
 __global__ __launch_bounds__(kBands) void fold_phasor_kernel(FoldArgs a)
 {
+    if ((int)blockIdx.x > a.S + 1) {
+        lane_phasor_entry(a.theta, ((int)blockIdx.x - a.S - 2) * kBands + (int)threadIdx.x, a.lane_table);
+        return;
+    }
     if ((int)blockIdx.x == a.S + 1) {   // uniform over the workgroup
-        if (a.work) build_work_list(a.seq_len, a.S, a.max_seq_len, a.work);
+        if (a.work) build_work_list(a.seq_len, a.S, a.max_seq_len, a.chunk_keys, a.work);
         return;
     }
     const int f = threadIdx.x;
@@ -272,24 +281,15 @@ __global__ __launch_bounds__(256) void stats_kernel(StatsArgs a)
         for (int t = r; t < tiles; t += 16) acc += a.partials[((int64_t)inst * a.n_tiles + t) * W + i];
     part[r][i] = acc;
     __syncthreads();
-    if (threadIdx.x < a.G) {
+    if (threadIdx.x < a.G) {   // (the same order of additions as tile_sum)
         const int g = threadIdx.x;
         double s1 = 0.0, s2 = 0.0;
         for (int k = 0; k < 16; ++k) {
             s1 += part[k][g];
             s2 += part[k][a.G + g];
         }
-        double mean = 0.0, rsig = 0.0;
-        if (N > 0) {
-            mean = s1 / (double)N;
-            double msq = s2 / (double)N;
-            double var = msq - mean * mean;
-            // Section 4.3 with sigma = 0: the head contributes 0.  The raw scores are fp32 sums of 192 products, so
-            // scores that are equal in exact arithmetic may differ in their last bits here (the same key scored
-            // against two different table bases), and the moments carry that noise: a spread below 3e-6 of the
-            // root mean square is not distinguishable from zero and is read as zero.
-            if (var > 1e-11 * msq) rsig = 1.0 / sqrt(var);
-        }
+        double mean, rsig;
+        moments_to_stats(s1, s2, N, &mean, &rsig);
         a.stats[((int64_t)inst * a.G + g) * 2 + 0] = mean;
         a.stats[((int64_t)inst * a.G + g) * 2 + 1] = rsig;
     }
@@ -360,6 +360,30 @@ tri_status launch_score_kernel(const tri_model &m, const ScoreArgs &sa, dim3 gri
     return hip_status("score_kernel");
 }
 
+// Compute units of the current GPU (asked once per GPU).
+tri_status device_cus(int *n_cu)
+{
+    constexpr int kDevices = 64;
+    static std::atomic<int> cached[kDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kDevices) {
+        (void)hipGetLastError();
+        set_error("score: no current device below %d", kDevices);
+        return TRI_ERR_HIP;
+    }
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            set_error("score: compute-unit count not available");
+            return TRI_ERR_HIP;
+        }
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    *n_cu = n;
+    return TRI_OK;
+}
+
 // MFMA kernel: bf16, a group of 16 slots never straddling a block, 32-bit row offsets
 bool mfma_path(const tri_cache &c, int G)
 {
@@ -369,18 +393,17 @@ bool mfma_path(const tri_cache &c, int G)
 
 template <int G>
 tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, const FinalArgs &fa,
-                          float *final_out, hipStream_t st)
+                          float *final_out, MomentLayout *moments, hipStream_t st)
 {
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
     const bool fast = mfma_path(c, G);
-    const int tile_keys = fast ? kFastChunk : kScoreTile;
+    const int tile_keys = fast ? sa.chunk_keys : kScoreTile;
     sa.n_tiles = (c.max_seq_len + tile_keys - 1) / tile_keys;
     tri_status rc = TRI_OK;
     // interleaved pairs: one key per lane; half-split pairs: the kernel that spreads a key over sixteen lanes
     const bool lane_kernel = fast && m.pairs == TRI_PAIR_INTERLEAVED;
-    if (fast && !c.k_rotated) {
-        rc = lane_kernel ? launch_lane_phasor_table(m.rope_theta, const_cast<uint4 *>(sa.phasors), st)
-                         : launch_phasor_table(m.rope_theta, const_cast<uint4 *>(sa.phasors), st);
+    if (fast && !lane_kernel && !c.k_rotated) {   // (the one-key-per-lane kernel's table came with the fold's phasors)
+        rc = launch_phasor_table(m.rope_theta, const_cast<uint4 *>(sa.phasors), st);
         if (rc != TRI_OK) return rc;
     }
     hipEvent_t ev0, ev1;
@@ -397,6 +420,11 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
     }
     if (timed) (void)hipEventRecord(ev1, st);
     if (rc != TRI_OK) return rc;
+    if (moments) {
+        moments->n_tiles = sa.n_tiles;
+        moments->tile_keys = tile_keys;
+    }
+    if (!final_out) return rc;   // fused step: the selection forms the statistics from the moments itself
     StatsArgs ta{sa.partials, const_cast<double *>(fa.stats), c.seq_len, c.n_seqs, m.n_kv_heads, sa.n_tiles, G,
                  tile_keys, c.max_seq_len};
     hipLaunchKernelGGL(stats_kernel, dim3(n_inst), dim3(256), 0, st, ta);
@@ -417,9 +445,10 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
 }  // namespace
 
 tri_status launch_score(const tri_model &m, const float *centers, const tri_cache &c, float *final_out,
-                        float *raw_out, char *ws, const Workspace &wl, hipStream_t st)
+                        float *raw_out, char *ws, const Workspace &wl, MomentLayout *moments, hipStream_t st)
 {
     const int G = m.n_q_heads / m.n_kv_heads;
+    if (moments) *moments = MomentLayout{1, 1};
     if (c.max_seq_len <= 0 || c.n_seqs <= 0) return TRI_OK;
     FoldArgs fo{};
     fo.centers = centers;
@@ -429,6 +458,15 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     fo.cur_pos = c.cur_pos;
     fo.seq_len = c.seq_len;
     fo.work = mfma_path(c, G) ? reinterpret_cast<int32_t *>(ws + wl.work) : nullptr;
+    // keys per work item: small batches on the one-key-per-lane kernel are cut finer
+    int chunk_keys = kFastChunk;
+    if (fo.work && m.pairs == TRI_PAIR_INTERLEAVED) {
+        int n_cu = 0;
+        tri_status rcu = device_cus(&n_cu);
+        if (rcu != TRI_OK) return rcu;
+        chunk_keys = lane_chunk_keys(G, (int64_t)m.n_layers * c.n_seqs * m.n_kv_heads, c.max_seq_len, n_cu);
+    }
+    fo.chunk_keys = chunk_keys;
     fo.max_seq_len = c.max_seq_len;
     fo.S = c.n_seqs;
     fo.Hq = m.n_q_heads;
@@ -438,7 +476,10 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     fo.n_off = m.n_offsets;
     fo.variant = m.score_variant;
     for (int j = 0; j < m.n_offsets; ++j) fo.offsets[j] = m.offsets[j];
-    hipLaunchKernelGGL(fold_phasor_kernel, dim3(2 + c.n_seqs), dim3(kBands), 0, st, fo);
+    const bool lane_table = fo.work && m.pairs == TRI_PAIR_INTERLEAVED && !c.k_rotated;
+    fo.lane_table = lane_table ? reinterpret_cast<float4 *>(ws + wl.phasors) : nullptr;
+    hipLaunchKernelGGL(fold_phasor_kernel, dim3(2 + c.n_seqs + (lane_table ? kLaneTableEntries / kBands : 0)),
+                       dim3(kBands), 0, st, fo);
     tri_status rc0 = hip_status("fold_phasor_kernel");
     if (rc0 != TRI_OK) return rc0;
     hipLaunchKernelGGL(fold_kernel, dim3(m.n_kv_heads, m.n_layers, (c.n_seqs + kFoldSeqs - 1) / kFoldSeqs),
@@ -455,17 +496,18 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     sa.phasors = reinterpret_cast<const uint4 *>(ws + wl.phasors);
     sa.work = reinterpret_cast<int32_t *>(ws + wl.work);
     sa.n_layers = m.n_layers;
+    sa.chunk_keys = chunk_keys;
     FinalArgs fa{sa.raw, reinterpret_cast<double *>(ws + wl.stats), final_out, c.seq_len, c.n_seqs,
                  m.n_kv_heads, c.max_seq_len, 0};
     switch (G) {
-        case 1: return launch_score_g<1>(m, c, sa, fa, final_out, st);
-        case 2: return launch_score_g<2>(m, c, sa, fa, final_out, st);
-        case 3: return launch_score_g<3>(m, c, sa, fa, final_out, st);
-        case 4: return launch_score_g<4>(m, c, sa, fa, final_out, st);
-        case 5: return launch_score_g<5>(m, c, sa, fa, final_out, st);
-        case 6: return launch_score_g<6>(m, c, sa, fa, final_out, st);
-        case 7: return launch_score_g<7>(m, c, sa, fa, final_out, st);
-        case 8: return launch_score_g<8>(m, c, sa, fa, final_out, st);
+        case 1: return launch_score_g<1>(m, c, sa, fa, final_out, moments, st);
+        case 2: return launch_score_g<2>(m, c, sa, fa, final_out, moments, st);
+        case 3: return launch_score_g<3>(m, c, sa, fa, final_out, moments, st);
+        case 4: return launch_score_g<4>(m, c, sa, fa, final_out, moments, st);
+        case 5: return launch_score_g<5>(m, c, sa, fa, final_out, moments, st);
+        case 6: return launch_score_g<6>(m, c, sa, fa, final_out, moments, st);
+        case 7: return launch_score_g<7>(m, c, sa, fa, final_out, moments, st);
+        case 8: return launch_score_g<8>(m, c, sa, fa, final_out, moments, st);
     }
     set_error("group size %d not built (1 to 8)", G);
     return TRI_ERR_UNSUPPORTED;

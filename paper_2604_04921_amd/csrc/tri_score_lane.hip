@@ -30,45 +30,21 @@ namespace tri {
 
 namespace {
 
-constexpr double kTwoPi = 6.283185307179586476925286766559;
 constexpr int kMaxDevices = 64;
 
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int kTileKeys = 64;
-constexpr int kLaneRange = 64;                                  // table holds relative positions 0 .. 63
-constexpr int kLanePairStride = kLaneRange * 16 + 16;           // bytes per band pair (16 bytes of skew)
-constexpr int kLanePhasorBytes = (kBands / 2) * kLanePairStride;
 constexpr int kStageBytes = kTileKeys * 128;                    // one half row per key, swizzled, no padding
 constexpr int kTabRow = kBands + 4;                             // floats per (component, head) row: 16 bytes of skew
 
-constexpr int lane_waves(int G) { return G > 4 ? 8 : 12; }      // LDS decides: 33 KB of phasors + a stage and a table per wave
+// (lane_waves(G): LDS decides -- 33 KB of phasors + a stage and a table per wave)
 constexpr int lane_heads(int G) { return 4 * ((G + 3) / 4); }   // table rows: query heads rounded up to whole quads
 constexpr int lane_wave_bytes(int G) { return kStageBytes + 2 * lane_heads(G) * kTabRow * 4; }   // stage + (re, im) rows
 constexpr int lane_lds_bytes(int G, bool rotated)
 {
     return (rotated ? 0 : kLanePhasorBytes) + lane_heads(G) * kTabRow * 4 + lane_waves(G) * lane_wave_bytes(G);
-}
-
-// grid (kBands / 2 * kLaneRange / 256), block 256: entry (band pair bp, r) = (cos, sin) of bands 2bp, 2bp+1 at relative
-// position r, evaluated in double, at byte bp * kLanePairStride + 16 r.
-__global__ __launch_bounds__(256) void lane_phasor_table_kernel(double theta, float4 *out)
-{
-    const int t = blockIdx.x * 256 + threadIdx.x;
-    const int r = t % kLaneRange, bp = t / kLaneRange;
-    if (bp >= kBands / 2) return;
-    float v[4];
-    for (int k = 0; k < 2; ++k) {
-        const int f = 2 * bp + k;
-        double x = (double)r * (pow(theta, -2.0 * (double)f / (double)kHeadDim) / kTwoPi);
-        x -= floor(x);
-        double s, c;
-        sincos(kTwoPi * x, &s, &c);
-        v[2 * k] = (float)c;
-        v[2 * k + 1] = (float)s;
-    }
-    out[bp * (kLanePairStride / 16) + r] = make_float4(v[0], v[1], v[2], v[3]);
 }
 
 __device__ __forceinline__ uint4 load_stream16(const char *p)
@@ -162,7 +138,7 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
         }
         __syncthreads();
 
-        const int c0 = chunk * kFastChunk, c_len = min(N - c0, kFastChunk);
+        const int c0 = chunk * a.chunk_keys, c_len = min(N - c0, a.chunk_keys);
         const int n_tiles = (c_len + kTileKeys - 1) / kTileKeys;
         const int Hq = c.n_kv_heads * G;
         float *rw = a.raw + (((int64_t)l * c.n_seqs + s) * Hq + (int64_t)h * G) * c.max_seq_len;
@@ -463,7 +439,7 @@ tri_status launch_lane_g(const ScoreArgs &sa, hipStream_t st)
     }
     const int64_t max_items = (int64_t)sa.n_tiles * sa.c.n_seqs * sa.c.n_kv_heads * sa.n_layers;
     if (max_items > (int64_t)0x7fff0000) {
-        set_error("score: %lld chunks of %d keys exceed the 32-bit work counter", (long long)max_items, kFastChunk);
+        set_error("score: %lld chunks of %d keys exceed the 32-bit work counter", (long long)max_items, sa.chunk_keys);
         return TRI_ERR_UNSUPPORTED;
     }
     const int grid = (int)std::min<int64_t>((int64_t)slots, max_items);
@@ -479,13 +455,6 @@ tri_status launch_lane_g(const ScoreArgs &sa, hipStream_t st)
 }
 
 }  // namespace
-
-tri_status launch_lane_phasor_table(double theta, uint4 *phasors, hipStream_t st)
-{
-    hipLaunchKernelGGL(lane_phasor_table_kernel, dim3((kBands / 2) * kLaneRange / 256), dim3(256), 0, st, theta,
-                       reinterpret_cast<float4 *>(phasors));
-    return hip_status("lane_phasor_table_kernel");
-}
 
 tri_status launch_score_lane(int G, const ScoreArgs &sa, hipStream_t st)
 {

@@ -210,7 +210,7 @@ __global__ __launch_bounds__(fast_threads(G), G > 4 ? 3 : 4) void score_mfma_ker
     const int l = lh / c.n_kv_heads, h = lh - l * c.n_kv_heads;
     const int s = __builtin_amdgcn_readfirstlane(a.work[kWorkHeader + 2 * wi]);
     const int chunk = __builtin_amdgcn_readfirstlane(a.work[kWorkHeader + 2 * wi + 1]);
-    const int N = clamp_len(c.seq_len[s], c.max_seq_len);   // chunk * kFastChunk < N by construction of the list
+    const int N = clamp_len(c.seq_len[s], c.max_seq_len);   // chunk * chunk_keys < N by construction of the list
 
     const int64_t inst = ((int64_t)l * c.n_seqs + s) * c.n_kv_heads + h;
     for (int k = tid; k < kBands * 3 * G; k += kFastThreads) lds_tab[k] = a.table[inst * (kBands * 3 * G) + k];
@@ -228,7 +228,7 @@ __global__ __launch_bounds__(fast_threads(G), G > 4 ? 3 : 4) void score_mfma_ker
             tb[q].cn[k] = on ? lds_tab[(f * 3 + 2) * G + g] : 0.f;
         }
 
-    const int c0 = chunk * kFastChunk, c_len = min(N - c0, kFastChunk);
+    const int c0 = chunk * a.chunk_keys, c_len = min(N - c0, a.chunk_keys);
     const int wave_keys = ((c_len + kFastWaves - 1) / kFastWaves + 15) & ~15;   // multiple of 16: groups stay aligned
     const int w0 = c0 + wave * wave_keys;
     const int w1 = min(w0 + wave_keys, c0 + c_len);

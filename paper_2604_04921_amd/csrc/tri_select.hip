@@ -30,7 +30,9 @@ __device__ __forceinline__ uint32_t order_key(float x)
 struct SelectArgs {
     const float *final_;   // [inst][Nmax] final scores, or NULL when raw + stats are given
     const float *raw;      // [inst][G][Nmax]
-    const double *stats;   // [inst][G][2] = (mean, 1/sigma)
+    const double *stats;   // [inst][G][2] = (mean, 1/sigma); unused when partials is given
+    const double *partials;   // [inst][n_tiles][2G] per-tile sum and sum of squares of the raw scores, or NULL
+    int32_t n_tiles, tile_keys;
     uint32_t *scratch;     // [inst][Nmax] keys of sequences too long for LDS (raw mode only)
     const int32_t *seq_len;
     int32_t *kept_idx;     // [inst][B]
@@ -92,9 +94,20 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
 
     ZParams zp[G > 0 ? G : 1];
     if constexpr (G > 0) {
+        __shared__ double zst[2 * (G > 0 ? G : 1)];
+        if (a.partials) {   // statistics from the moments (uniform over the launch)
+            if (tid < G) {
+                const double *col = a.partials + (int64_t)inst * a.n_tiles * (2 * G);
+                const int tiles = (N + a.tile_keys - 1) / a.tile_keys;
+                moments_to_stats(tile_sum(col + tid, tiles, 2 * G), tile_sum(col + G + tid, tiles, 2 * G), N,
+                                 &zst[2 * tid], &zst[2 * tid + 1]);
+            }
+            __syncthreads();
+        }
 #pragma unroll
         for (int g = 0; g < G; ++g)
-            zp[g] = z_params(a.stats[((int64_t)inst * G + g) * 2], a.stats[((int64_t)inst * G + g) * 2 + 1]);
+            zp[g] = a.partials ? z_params(zst[2 * g], zst[2 * g + 1])
+                               : z_params(a.stats[((int64_t)inst * G + g) * 2], a.stats[((int64_t)inst * G + g) * 2 + 1]);
     }
     // key of slot n from its source (first touch)
     auto make_key = [&](int n) {
@@ -305,6 +318,15 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
     }
     for (int k = tid; k < kSelBins; k += THREADS) hist[k] = 0u;
     if (tid < 36) sh[tid] = 0u;
+    __shared__ double zst[2 * (G > 0 ? G : 1)];
+    if constexpr (G > 0) {
+        if (a.partials && tid < G) {   // statistics from the moments
+            const double *col = a.partials + (int64_t)inst * a.n_tiles * (2 * G);
+            const int tiles = (N + a.tile_keys - 1) / a.tile_keys;
+            moments_to_stats(tile_sum(col + tid, tiles, 2 * G), tile_sum(col + G + tid, tiles, 2 * G), N,
+                             &zst[2 * tid], &zst[2 * tid + 1]);
+        }
+    }
     __syncthreads();
 
     // ---- keys into registers, histogram of their linear bins.  A slot past the end holds key 0, which no finite
@@ -318,7 +340,8 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
         if constexpr (G > 0) {
 #pragma unroll
             for (int g = 0; g < G; ++g)
-                zp[g] = z_params(a.stats[((int64_t)inst * G + g) * 2], a.stats[((int64_t)inst * G + g) * 2 + 1]);
+                zp[g] = a.partials ? z_params(zst[2 * g], zst[2 * g + 1])
+                                   : z_params(a.stats[((int64_t)inst * G + g) * 2], a.stats[((int64_t)inst * G + g) * 2 + 1]);
         }
         // Rows are taken 16 at a time (fewer with many query heads, and in the 256-thread variant, whose occupancy
         // depends on its register count; measured: 16 rows 729 us on config 3, was 940; 8 rows 216 us at steady state,
@@ -541,12 +564,13 @@ tri_status launch_select_g(const SelectArgs &sa, int n_inst, hipStream_t st)
 }  // namespace
 
 tri_status launch_select(const tri_model &m, const float *final_scores, const float *raw, const double *stats,
-                         uint32_t *scratch, const tri_cache &c, int32_t budget, int32_t *kept_idx,
-                         int32_t *kept_cnt, hipStream_t st)
+                         const double *partials, MomentLayout moments, uint32_t *scratch, const tri_cache &c,
+                         int32_t budget, int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st)
 {
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
     if (n_inst <= 0) return TRI_OK;
-    SelectArgs sa{final_scores, raw, stats, scratch, c.seq_len, kept_idx, kept_cnt, c.n_seqs, m.n_kv_heads,
+    SelectArgs sa{final_scores, raw, stats, partials, moments.n_tiles, moments.tile_keys, scratch, c.seq_len, kept_idx,
+                  kept_cnt, c.n_seqs, m.n_kv_heads,
                   c.max_seq_len, budget, c.max_seq_len < kSelLdsKeys ? (c.max_seq_len > 0 ? c.max_seq_len : 1) : kSelLdsKeys,
                   m.head_budgets, -1, c.max_seq_len};
     if (final_scores) return launch_select_g<0>(sa, n_inst, st);
