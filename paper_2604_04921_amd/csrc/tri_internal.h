@@ -59,19 +59,8 @@ __device__ __forceinline__ ZParams z_params(double mu, double inv_sigma)
 __device__ __forceinline__ float z_score(float raw, const ZParams &p) { return ((raw - p.mu_hi) - p.mu_lo) * p.rs; }
 
 // Section 4.3, mu_g and 1/sigma_g of one query head from the per-tile sums of its raw scores and of their squares.
-// `col` points at the head's entry of the head-instance's first tile, entries of successive tiles lie `stride`
-// doubles apart.  The tiles are added in sixteen interleaved groups and the groups in order: stats_kernel (one thread
-// per group) and the selection kernels (one thread per head) both call this, so both get the same bits.
-__device__ __forceinline__ double tile_sum(const double *col, int tiles, int stride)
-{
-    double tot = 0.0;
-    for (int k = 0; k < 16; ++k) {
-        double acc = 0.0;
-        for (int t = k; t < tiles; t += 16) acc += col[(int64_t)t * stride];
-        tot += acc;
-    }
-    return tot;
-}
+// The tiles are added in sixteen interleaved groups (one thread each) and the groups in order, in stats_kernel and
+// in the selection kernels (block_stats) alike, so both get the same bits.
 __device__ __forceinline__ void moments_to_stats(double s1, double s2, int N, double *mean_out, double *rsig_out)
 {
     double mean = 0.0, rsig = 0.0;
@@ -87,6 +76,30 @@ __device__ __forceinline__ void moments_to_stats(double s1, double s2, int N, do
     }
     *mean_out = mean;
     *rsig_out = rsig;
+}
+
+// Statistics of a head-instance's G query heads inside a workgroup of at least 32 G threads: pt = the
+// head-instance's [tiles][2G] moments, part = 32 G doubles and zst = 2 G doubles of LDS; on return (after a barrier)
+// zst[2g], zst[2g + 1] = mean and 1/sigma of head g.
+template <int G>
+__device__ __forceinline__ void block_stats(const double *pt, int tiles, int N, int tid, double *part, double *zst)
+{
+    if (tid < 2 * G * 16) {
+        const int col = tid >> 4, k = tid & 15;
+        double acc = 0.0;
+        for (int t = k; t < tiles; t += 16) acc += pt[(int64_t)t * (2 * G) + col];
+        part[col * 16 + k] = acc;
+    }
+    __syncthreads();
+    if (tid < G) {
+        double s1 = 0.0, s2 = 0.0;
+        for (int k = 0; k < 16; ++k) {
+            s1 += part[tid * 16 + k];
+            s2 += part[(G + tid) * 16 + k];
+        }
+        moments_to_stats(s1, s2, N, &zst[2 * tid], &zst[2 * tid + 1]);
+    }
+    __syncthreads();
 }
 
 // Element offset of slot n of (layer, seq, head) in k / v.

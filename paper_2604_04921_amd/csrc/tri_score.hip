@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256) void stats_kernel(StatsArgs a)
         for (int t = r; t < tiles; t += 16) acc += a.partials[((int64_t)inst * a.n_tiles + t) * W + i];
     part[r][i] = acc;
     __syncthreads();
-    if (threadIdx.x < a.G) {   // (the same order of additions as tile_sum)
+    if (threadIdx.x < a.G) {   // (the same order of additions as block_stats)
         const int g = threadIdx.x;
         double s1 = 0.0, s2 = 0.0;
         for (int k = 0; k < 16; ++k) {
@@ -393,15 +393,13 @@ bool mfma_path(const tri_cache &c, int G)
 
 template <int G>
 tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, const FinalArgs &fa,
-                          float *final_out, MomentLayout *moments, hipStream_t st)
+                          float *final_out, MomentLayout *moments, bool lane_kernel, hipStream_t st)
 {
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
     const bool fast = mfma_path(c, G);
     const int tile_keys = fast ? sa.chunk_keys : kScoreTile;
     sa.n_tiles = (c.max_seq_len + tile_keys - 1) / tile_keys;
     tri_status rc = TRI_OK;
-    // interleaved pairs: one key per lane; half-split pairs: the kernel that spreads a key over sixteen lanes
-    const bool lane_kernel = fast && m.pairs == TRI_PAIR_INTERLEAVED;
     if (fast && !lane_kernel && !c.k_rotated) {   // (the one-key-per-lane kernel's table came with the fold's phasors)
         rc = launch_phasor_table(m.rope_theta, const_cast<uint4 *>(sa.phasors), st);
         if (rc != TRI_OK) return rc;
@@ -476,7 +474,12 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     fo.n_off = m.n_offsets;
     fo.variant = m.score_variant;
     for (int j = 0; j < m.n_offsets; ++j) fo.offsets[j] = m.offsets[j];
-    const bool lane_table = fo.work && m.pairs == TRI_PAIR_INTERLEAVED && !c.k_rotated;
+    // Interleaved pairs: the kernel with one key per lane.  Paged caches go there only as small batches (work items
+    // below kFastChunk, which only that kernel takes): on large paged batches the kernel that spreads a key over
+    // sixteen lanes is 3 % faster (config 4: 12.2 ms against 12.5 ms per 12-layer slab), as it is the only one for
+    // half-split pairs.
+    const bool lane_kernel = fo.work && m.pairs == TRI_PAIR_INTERLEAVED && (c.block_size == 0 || chunk_keys < kFastChunk);
+    const bool lane_table = lane_kernel && !c.k_rotated;
     fo.lane_table = lane_table ? reinterpret_cast<float4 *>(ws + wl.phasors) : nullptr;
     hipLaunchKernelGGL(fold_phasor_kernel, dim3(2 + c.n_seqs + (lane_table ? kLaneTableEntries / kBands : 0)),
                        dim3(kBands), 0, st, fo);
@@ -500,14 +503,14 @@ tri_status launch_score(const tri_model &m, const float *centers, const tri_cach
     FinalArgs fa{sa.raw, reinterpret_cast<double *>(ws + wl.stats), final_out, c.seq_len, c.n_seqs,
                  m.n_kv_heads, c.max_seq_len, 0};
     switch (G) {
-        case 1: return launch_score_g<1>(m, c, sa, fa, final_out, moments, st);
-        case 2: return launch_score_g<2>(m, c, sa, fa, final_out, moments, st);
-        case 3: return launch_score_g<3>(m, c, sa, fa, final_out, moments, st);
-        case 4: return launch_score_g<4>(m, c, sa, fa, final_out, moments, st);
-        case 5: return launch_score_g<5>(m, c, sa, fa, final_out, moments, st);
-        case 6: return launch_score_g<6>(m, c, sa, fa, final_out, moments, st);
-        case 7: return launch_score_g<7>(m, c, sa, fa, final_out, moments, st);
-        case 8: return launch_score_g<8>(m, c, sa, fa, final_out, moments, st);
+        case 1: return launch_score_g<1>(m, c, sa, fa, final_out, moments, lane_kernel, st);
+        case 2: return launch_score_g<2>(m, c, sa, fa, final_out, moments, lane_kernel, st);
+        case 3: return launch_score_g<3>(m, c, sa, fa, final_out, moments, lane_kernel, st);
+        case 4: return launch_score_g<4>(m, c, sa, fa, final_out, moments, lane_kernel, st);
+        case 5: return launch_score_g<5>(m, c, sa, fa, final_out, moments, lane_kernel, st);
+        case 6: return launch_score_g<6>(m, c, sa, fa, final_out, moments, lane_kernel, st);
+        case 7: return launch_score_g<7>(m, c, sa, fa, final_out, moments, lane_kernel, st);
+        case 8: return launch_score_g<8>(m, c, sa, fa, final_out, moments, lane_kernel, st);
     }
     set_error("group size %d not built (1 to 8)", G);
     return TRI_ERR_UNSUPPORTED;

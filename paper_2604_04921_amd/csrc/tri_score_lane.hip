@@ -118,26 +118,6 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
         const int64_t inst = ((int64_t)l * c.n_seqs + s) * c.n_kv_heads + h;
         const float *tbl = a.table + inst * (kBands * 3 * G);   // [F][3][G]
 
-        // norm-term rows of this head-instance (shared), and the lane's own band of the folded table (lane = band)
-        for (int k = tid; k < kBands * G; k += kThreads) {
-            const int f = k / G, g = k - f * G;
-            reinterpret_cast<float *>(cn_base)[g * kTabRow + f] = tbl[(f * 3 + 2) * G + g];
-        }
-        for (int k = tid; k < kBands * G; k += kThreads) {
-            const int f = k / G, g = k - f * G;
-            const float re = tbl[(f * 3 + 0) * G + g], im = tbl[(f * 3 + 1) * G + g];
-            q_tab[0][g][f] = re;
-            q_tab[1][g][f] = im;
-            if constexpr (ROTATED) {   // no base to fold in: every wave's copy is written once per item
-                for (int w = 0; w < W; ++w) {
-                    char *const wb = cn_base + kTabBytes + w * lane_wave_bytes(G) + kStageBytes;
-                    reinterpret_cast<float *>(wb)[g * kTabRow + f] = re;
-                    reinterpret_cast<float *>(wb + kTabBytes)[g * kTabRow + f] = im;
-                }
-            }
-        }
-        __syncthreads();
-
         const int c0 = chunk * a.chunk_keys, c_len = min(N - c0, a.chunk_keys);
         const int n_tiles = (c_len + kTileKeys - 1) / kTileKeys;
         const int Hq = c.n_kv_heads * G;
@@ -153,20 +133,25 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
         // half row `half` of the tile at slot n0 (cnt keys exist): eight 16-byte loads per lane.  For a whole tile every
         // address is a wave-uniform pointer (a group of eight keys never straddles a block) plus the lane's constant
         // offset; in the last, partial tile a key past the end repeats the last one.
-        auto load_half = [&](int n0, int cnt, int half, uint4(&kd)[8]) {
+        // Paged caches: lane j of `btv` holds the physical block of keys n0 + 16 j .. + 15 (load_blocks; a block holds
+        // 16 slots or more), asked for a tile ahead like the positions, so that no load here waits for a block-table
+        // entry.
+        auto load_half = [&](int n0, int cnt, int half, uint4(&kd)[8], int btv) {
             if (cnt == kTileKeys) {
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
+                for (int t = 0; t < 8; t += 2) {
                     const int n = n0 + 8 * t;
                     const char *p;
                     if constexpr (PAGED) {
-                        const int blk = __builtin_amdgcn_readfirstlane(bt[n >> c.block_shift]);
+                        const int blk = __builtin_amdgcn_readlane(btv, t / 2);
                         p = krow + (int64_t)blk * c.stride_sb * 2 + (int64_t)(n & bmask) * slot_bytes;
                     } else {
                         p = krow + (int64_t)n * slot_bytes;
                     }
                     asm volatile("" : "+v"(ld_off));   // keeps (scalar base + 32-bit lane offset) addressing
                     kd[t] = load_stream16(p + half * 128 + ld_off);
+                    asm volatile("" : "+v"(ld_off));
+                    kd[t + 1] = load_stream16(p + 8 * (int64_t)slot_bytes + half * 128 + ld_off);
                 }
             } else {
 #pragma unroll
@@ -182,6 +167,10 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
                     kd[t] = load_stream16(p + half * 128 + ld_piece * 16);
                 }
             }
+        };
+        auto load_blocks = [&](int n0, int cnt) -> int {
+            if constexpr (!PAGED) return 0;
+            return bt[(n0 + min(16 * (lane & 3), cnt - 1)) >> c.block_shift];
         };
         auto load_pos = [&](int n0, int cnt) -> int {
             if constexpr (ROTATED) return 0;
@@ -204,16 +193,42 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
 
         int t_idx = wave;
         uint4 kd[8];
-        int pos_next = 0;
+        int pos_next = 0, bt_cur = 0, bt_next = 0;
         if (t_idx < n_tiles) {
             const int n0 = c0 + t_idx * kTileKeys;
-            load_half(n0, min(kTileKeys, c0 + c_len - n0), 0, kd);
+            bt_cur = load_blocks(n0, min(kTileKeys, c0 + c_len - n0));
+            load_half(n0, min(kTileKeys, c0 + c_len - n0), 0, kd, bt_cur);
             pos_next = load_pos(n0, min(kTileKeys, c0 + c_len - n0));
         }
+        // (the first tile's loads are on their way)  Norm-term rows of this head-instance, shared by the waves, and the
+        // folded table per band
+        for (int k = tid; k < kBands * G; k += kThreads) {
+            const int f = k / G, g = k - f * G;
+            reinterpret_cast<float *>(cn_base)[g * kTabRow + f] = tbl[(f * 3 + 2) * G + g];
+        }
+        for (int k = tid; k < kBands * G; k += kThreads) {
+            const int f = k / G, g = k - f * G;
+            const float re = tbl[(f * 3 + 0) * G + g], im = tbl[(f * 3 + 1) * G + g];
+            q_tab[0][g][f] = re;
+            q_tab[1][g][f] = im;
+            if constexpr (ROTATED) {   // no base to fold in: every wave's copy is written once per item
+                for (int w = 0; w < W; ++w) {
+                    char *const wb = cn_base + kTabBytes + w * lane_wave_bytes(G) + kStageBytes;
+                    reinterpret_cast<float *>(wb)[g * kTabRow + f] = re;
+                    reinterpret_cast<float *>(wb + kTabBytes)[g * kTabRow + f] = im;
+                }
+            }
+        }
+        __syncthreads();
+
         for (; t_idx < n_tiles; t_idx += W) {
             const int n0 = c0 + t_idx * kTileKeys;
             const int cnt = min(kTileKeys, c0 + c_len - n0);
             const int p_key = pos_next;
+            if (t_idx + W < n_tiles) {   // the next tile's blocks: needed when its first loads go out, half a tile from now
+                const int m0 = c0 + (t_idx + W) * kTileKeys;
+                bt_next = load_blocks(m0, min(kTileKeys, c0 + c_len - m0));
+            }
 
             // ---- the tile's base and the lane's relative position
             int r = 0;
@@ -340,10 +355,10 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
                     stage_half(kd);   // waits for the half row's loads, then 8 LDS writes
                     // the next loads go out while this half row is scored
                     if (half == 0) {
-                        load_half(n0, cnt, 1, kd);
+                        load_half(n0, cnt, 1, kd, bt_cur);
                     } else if (t_idx + W < n_tiles) {
                         const int m0 = c0 + (t_idx + W) * kTileKeys, mc = min(kTileKeys, c0 + c_len - m0);
-                        load_half(m0, mc, 0, kd);
+                        load_half(m0, mc, 0, kd, bt_next);
                         pos_next = load_pos(m0, mc);
                     }
                     Piece cur = fetch(half, 0, table_tag);
@@ -360,6 +375,7 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
             else if (mirrored) score_tile(std::true_type{}, std::true_type{});
             else score_tile(std::true_type{}, std::false_type{});
 
+            bt_cur = bt_next;
             // ---- lane (b, j) holds keys n0 + 4b .. + 3 for head 4q + j
 #pragma unroll
             for (int q = 0; q < NG; ++q) {

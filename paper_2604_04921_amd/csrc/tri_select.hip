@@ -94,16 +94,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectArgs a)
 
     ZParams zp[G > 0 ? G : 1];
     if constexpr (G > 0) {
-        __shared__ double zst[2 * (G > 0 ? G : 1)];
-        if (a.partials) {   // statistics from the moments (uniform over the launch)
-            if (tid < G) {
-                const double *col = a.partials + (int64_t)inst * a.n_tiles * (2 * G);
-                const int tiles = (N + a.tile_keys - 1) / a.tile_keys;
-                moments_to_stats(tile_sum(col + tid, tiles, 2 * G), tile_sum(col + G + tid, tiles, 2 * G), N,
-                                 &zst[2 * tid], &zst[2 * tid + 1]);
-            }
-            __syncthreads();
-        }
+        __shared__ double zst[2 * (G > 0 ? G : 1)], zpart[32 * (G > 0 ? G : 1)];
+        if (a.partials)   // statistics from the moments (uniform over the launch)
+            block_stats<G>(a.partials + (int64_t)inst * a.n_tiles * (2 * G), (N + a.tile_keys - 1) / a.tile_keys, N, tid,
+                           zpart, zst);
 #pragma unroll
         for (int g = 0; g < G; ++g)
             zp[g] = a.partials ? z_params(zst[2 * g], zst[2 * g + 1])
@@ -318,14 +312,11 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
     }
     for (int k = tid; k < kSelBins; k += THREADS) hist[k] = 0u;
     if (tid < 36) sh[tid] = 0u;
-    __shared__ double zst[2 * (G > 0 ? G : 1)];
+    __shared__ double zst[2 * (G > 0 ? G : 1)], zpart[32 * (G > 0 ? G : 1)];
     if constexpr (G > 0) {
-        if (a.partials && tid < G) {   // statistics from the moments
-            const double *col = a.partials + (int64_t)inst * a.n_tiles * (2 * G);
-            const int tiles = (N + a.tile_keys - 1) / a.tile_keys;
-            moments_to_stats(tile_sum(col + tid, tiles, 2 * G), tile_sum(col + G + tid, tiles, 2 * G), N,
-                             &zst[2 * tid], &zst[2 * tid + 1]);
-        }
+        if (a.partials)   // statistics from the moments (uniform over the launch)
+            block_stats<G>(a.partials + (int64_t)inst * a.n_tiles * (2 * G), (N + a.tile_keys - 1) / a.tile_keys, N, tid,
+                           zpart, zst);
     }
     __syncthreads();
 
