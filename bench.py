@@ -23,7 +23,7 @@ STEP_BYTES = lambda n, b: 260 * n + 1032 * min(n, b)   # + survivors' K, V, pos 
 # each scaled by what the same counter reads for a plain device copy of known size: FETCH_SIZE reads 0.5 of the
 # bytes a 1 GiB copy fetches, WRITE_SIZE 1.0); summary in profiles/pmc_traffic_c3_model.md.  The figure belongs to
 # the kernel sources it was measured on: it is reported only while their hash (kernel_sources_sha16) is unchanged.
-MEASURED_TRAFFIC = {"c3_model/dense": {"bytes": 39.80e9 + 2.43e9, "sources_sha16": "unmeasured"}}
+MEASURED_TRAFFIC = {"c3_model/dense": {"bytes": 39.29e9 + 2.42e9, "sources_sha16": "d3e31d16b588a671"}}
 
 
 def kernel_sources_sha16():
@@ -203,8 +203,16 @@ def main():
     if args.fill and step_bytes:   # only the kept keys stored beyond the new length move
         moved = int((kept_idx >= kept_cnt[..., None]).sum())
         step_bytes = 260 * keys + 1032 * moved
-    mfma_path = eb == 2 and (cfg.block_size == 0 or cfg.block_size >= 16)   # which of the two score kernels ran
-    roofline = {"bound": "hbm", "kernel": "score_mfma_kernel" if mfma_path else "score_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+    # which of the three score kernels ran (the library's dispatch rule, restated for the label only): bf16 keys in
+    # blocks of 16 or more go to an MFMA kernel; of those, interleaved pairs to the one-key-per-lane kernel unless the
+    # cache is paged and the batch large enough for 8192-key work items
+    mfma_path = eb == 2 and (cfg.block_size == 0 or cfg.block_size >= 16)
+    waves = 8 if Hq // Hkv > 4 else 12
+    rounds = (L * S * Hkv * ((cfg.seq_len + 63) // 64)) // (4 * torch.cuda.get_device_properties(0).multi_processor_count * waves)
+    small_items = rounds * waves * 64 < 8192
+    lane = mfma_path and not args.half_split and (cfg.block_size == 0 or small_items)
+    kernel = "score_lane_kernel" if lane else "score_mfma_kernel" if mfma_path else "score_kernel"
+    roofline = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": measured_traffic(cfg.name, mode, args),
                 "launch_ms": round(launch_ms, 4), "launches_per_step": launches,

@@ -151,7 +151,9 @@ def test_c2_layer_full(oracle):
 def test_c3_model_full(oracle, positions):
     """Config 3: 36 layers x 16 sequences x 8 KV heads x 32768 keys, the benchmark workload."""
     cfg = recipe.CONFIGS["c3_model"]
-    run_full(oracle, cfg, [(0, 0, 0), (17, 5, 3), (35, 15, 7)], positions=positions)
+    n = 16 if positions == "dense" else 8   # head-instances through the oracle, spread over layers, sequences, heads
+    picks = [(0, 0, 0), (35, 15, 7)] + [((7 * i + 3) % 36, (5 * i + 1) % 16, (3 * i + 2) % 8) for i in range(n - 2)]
+    run_full(oracle, cfg, picks, positions=positions)
 
 
 @pytest.mark.parametrize("slab", [0, 1, 2])
