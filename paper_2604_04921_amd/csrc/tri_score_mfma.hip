@@ -1,5 +1,7 @@
-// Score kernel for bf16 keys (interleaved or half-split pairs): fp32 MFMA for the contraction over
-// (band, component) x query head, a phasor table in LDS for the rotation of the key.
+// Score kernel for bf16 keys with a key spread over sixteen lanes: fp32 MFMA for the contraction over
+// (band, component) x query head, a phasor table in LDS for the rotation of the key.  It takes interleaved or
+// half-split pairs; the launcher in tri_score.hip sends it the half-split caches and the large paged batches
+// (the one-key-per-lane kernel of tri_score_lane.hip takes the rest).
 //
 // Lane layout (wave64): lane = 4*b + i.  In one step a wave scores 4 keys; lane (b, i) loads the
 // 16 bytes holding bands 4b..4b+3 of key i -- exactly the operand layout of

@@ -2,9 +2,9 @@
 // image of the float score, then an ordered emit so that the kept slots come out ascending and equal
 // scores at the threshold go to the lower slots.
 //
-// Either kernel takes final scores (tri_select_topk) or takes the raw per-head scores and the
-// per-head mean / 1/sigma and forms S_final = max_g (S~(g) - mu_g) / sigma_g itself (fused step:
-// the final scores then never travel through memory).  Sequences of up to 32768 keys keep their
+// Either kernel takes final scores (tri_select_topk) or takes the raw per-head scores and their
+// per-chunk moments (or ready-made mean / 1/sigma), forms the statistics and S_final = max_g (S~(g) - mu_g) /
+// sigma_g itself (fused step: neither statistics nor final scores then travel through memory).  Sequences of up to 32768 keys keep their
 // integer keys in registers (select_reg_kernel: one histogram over linear score bins, exact ranking of
 // the threshold bin); longer ones use select_kernel (the same steps over keys held in LDS or, beyond
 // 32768 keys, in a workspace area).
