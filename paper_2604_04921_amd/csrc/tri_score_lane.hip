@@ -266,9 +266,9 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
             }
             const char *ph_lane = ph_base + r * 16;
 
-            float4v acc[NG];
+            float4v acc[NG], acc2[NG];   // two chains, so that consecutive matrix instructions do not depend on each other
 #pragma unroll
-            for (int q = 0; q < NG; ++q) acc[q] = float4v{0.f, 0.f, 0.f, 0.f};
+            for (int q = 0; q < NG; ++q) acc[q] = acc2[q] = float4v{0.f, 0.f, 0.f, 0.f};
 
             // Everything a piece (four bands of the lane's key) needs from LDS: the key's 16 bytes, the phasors of its
             // four bands at the lane's relative position, the lane's table entries.  Pieces are fetched one ahead of
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
 #pragma unroll
                     for (int q = 0; q < NG; ++q) {
                         const float t_[4] = {pz.bi[q].x, pz.bi[q].y, pz.bi[q].z, pz.bi[q].w};
-                        acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(ki[k], t_[k], acc[q], 0, 0, 0);
+                        acc2[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(ki[k], t_[k], acc2[q], 0, 0, 0);
                     }
 #pragma unroll
                     for (int q = 0; q < NG; ++q) {
@@ -376,6 +376,8 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
             else score_tile(std::true_type{}, std::false_type{});
 
             bt_cur = bt_next;
+#pragma unroll
+            for (int q = 0; q < NG; ++q) acc[q] += acc2[q];
             // ---- lane (b, j) holds keys n0 + 4b .. + 3 for head 4q + j
 #pragma unroll
             for (int q = 0; q < NG; ++q) {
