@@ -334,13 +334,27 @@ def test_many_short_sequences(oracle):
 
 
 def test_chunk_boundaries(oracle):
-    """Sequence lengths around the 8192-key chunk of the score kernel: one key short of a chunk, exactly one chunk,
-    one key more, and two chunks plus a ragged tail."""
-    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=4, n_q_heads=8, n_kv_heads=1, seq_len=16901,
+    """Sequence lengths around the work items of the score kernel.  A batch this small is cut into items of one round
+    of the kernel's waves (768 keys): one key short of an item, exactly one, one more; and lengths around 8192 keys and
+    two of them plus a ragged tail."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=7, n_q_heads=8, n_kv_heads=1, seq_len=16901,
                         min_seq_len=16901, budget=500, n_calib=128)
     def lens(w):
-        w["seq_len"][:] = np.array([8191, 8192, 8193, 16901], dtype=np.int32)
+        w["seq_len"][:] = np.array([767, 768, 769, 8191, 8192, 8193, 16901], dtype=np.int32)
     run_and_check(oracle, cfg, mutate=lens)
+
+
+def test_work_items_of_two_rounds(oracle):
+    """A batch large enough for work items of two rounds (1536 keys) and small enough not to reach the full 8192:
+    2 layers x 16 sequences x 8 KV heads of up to 6200 keys, lengths around the item size; a dozen head-instances go
+    through the oracle, all of them through the compaction check's index rules."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=2, n_seqs=16, n_q_heads=32, n_kv_heads=8, seq_len=6200,
+                        min_seq_len=6200, budget=300, n_calib=128)
+    def lens(w):
+        w["seq_len"][:] = np.array([1535, 1536, 1537, 3071, 3072, 3073, 4608, 6200, 6144, 100, 0, 1600, 5000, 2999, 64, 6199],
+                                   dtype=np.int32)
+    picks = [(l, s, (3 * s + l) % 8) for l in range(2) for s in (0, 1, 2, 5, 7, 8)]
+    run_and_check(oracle, cfg, mutate=lens, instances=picks)
 
 
 def test_all_sequences_empty():
