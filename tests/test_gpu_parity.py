@@ -373,3 +373,46 @@ def test_all_sequences_empty():
     assert run.kept_cnt.cpu().numpy().tolist() == [[[0, 0]] * 3] * 2
     assert run.new_len.cpu().numpy().tolist() == [0, 0, 0]
     assert torch.equal(run.k.view(torch.int16), k0.view(torch.int16))
+
+
+def test_repeated_calls_give_the_same_bits():
+    """Work items reach the workgroups through a shared counter, in an order that differs from launch to launch; the
+    raw and final scores, the moments behind them and the kept sets must not depend on it.  4 x 16 x 8 head-instances
+    of ragged lengths up to 20000 keys generated on the device (work items of 8192 keys and shorter last ones, about six
+    per workgroup the GPU holds), five calls of tri_score and of the fused step compared bit for bit."""
+    from paper_2604_04921_amd import binding as B
+    from workload import device
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=4, n_seqs=16, n_q_heads=32, n_kv_heads=8, seq_len=20000,
+                        min_seq_len=3000, budget=1024, n_calib=128)
+    w = device.generate(cfg, positions="sparse", layers=cfg.n_layers)
+    L, S, Hq, Hkv, d, Bk = cfg.n_layers, cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.budget
+    model = B.Model(L, Hq, Hkv, d, cfg.rope_theta, cfg.offsets)
+    src = B.Cache(w["k"], w["v"], w["pos"], w["seq_len"], w["cur_pos"], cfg.seq_len, None)
+    centers = torch.empty((L, Hq, d // 2, 3), dtype=torch.float32, device="cuda")
+    B.tri_build_centers(model, w["q_samples"], centers)
+    kd = torch.zeros((L, S, Hkv, Bk, d), dtype=w["k"].dtype, device="cuda")
+    vd, pd = torch.zeros_like(kd), torch.zeros((L, S, Hkv, Bk), dtype=torch.int32, device="cuda")
+    dst = B.Cache(kd, vd, pd, w["seq_len"], w["cur_pos"], Bk)
+    final = torch.empty((L, S, Hkv, cfg.seq_len), dtype=torch.float32, device="cuda")
+    raw = torch.empty((L, S, Hq, cfg.seq_len), dtype=torch.float32, device="cuda")
+    kept_idx = torch.empty((L, S, Hkv, Bk), dtype=torch.int32, device="cuda")
+    kept_cnt = torch.empty((L, S, Hkv), dtype=torch.int32, device="cuda")
+    new_len = torch.empty((S,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.tri_workspace_size(model, src, Bk), dtype=torch.uint8, device="cuda")
+    first = None
+    for rep in range(5):
+        final.fill_(float("nan"))
+        raw.fill_(float("nan"))
+        kept_idx.fill_(-1)
+        B.tri_score(model, centers, src, final, raw, ws)
+        B.tri_compress_step(model, centers, src, dst, Bk, kept_idx, kept_cnt, new_len, ws)
+        torch.cuda.synchronize()
+        got = [final.clone().view(torch.int32), raw.clone().view(torch.int32), kept_idx.clone(), kept_cnt.clone(),
+               kd.clone().view(torch.int16)]
+        if first is None:
+            first = got
+            assert int(kept_cnt.min()) == Bk and int(kept_cnt.max()) == Bk
+            assert not bool(torch.isnan(raw[0, 0, 0, :3000]).any())
+        else:
+            for a, b in zip(first, got):
+                assert torch.equal(a, b), "call %d differs from the first" % rep
