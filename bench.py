@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--config", default="c3_model")
     ap.add_argument("--positions", default=None, choices=[None, "dense", "sparse", "sparse16", "scattered"])
     ap.add_argument("--layers", type=int, default=None, help="layer slab (configurations larger than HBM)")
+    ap.add_argument("--slabs", type=int, default=1,
+                    help="with --layers: run this many consecutive layer slabs one after the other (each generated, "
+                         "measured and freed in turn) and report them as one step over slabs x layers layers")
     ap.add_argument("--seqs", type=int, default=None, help="number of sequences instead of the configuration's")
     ap.add_argument("--cpu-instances", type=int, default=32, help="head-instances the CPU oracle is timed on")
     ap.add_argument("--no-cpu", action="store_true")
@@ -90,9 +93,76 @@ def main():
         cfg = recipe.scaled(cfg, n_seqs=args.seqs)
     mode = args.positions or cfg.positions
     L = args.layers or cfg.n_layers
+    if args.slabs < 1 or (args.slabs > 1 and not args.layers) or args.slabs * L > max(cfg.n_layers, L):
+        print("bench.py: --slabs needs --layers, and slabs x layers may not exceed the configuration's layers", file=sys.stderr)
+        sys.exit(2)
+    if args.slabs > 1:
+        args.no_cpu = True   # the oracle's sample and the kept sets it is compared with belong to one slab
+    parts = [measure(args, cfg, mode, L, i * L) for i in range(args.slabs)]
+    m = parts[0]
+    S, Hq, Hkv, B, d = cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads, cfg.budget, cfg.head_dim
+    paged, in_place, launches, t_gen = m["paged"], m["in_place"], sum(p_["launches"] for p_ in parts), sum(p_["t_gen"] for p_ in parts)
+    lens = m["lens"]
+    keys = sum(p_["keys"] for p_ in parts)
+    ms = sum(p_["elapsed"] for p_ in parts) * 1e3 / args.steps
+    value = keys / (ms * 1e-3) / 1e9
+    # one step makes `launches` score launches (one per slab); their mean durations add up to the step's score time
+    launch_ms = float(sum(np.mean(p_["k_ms"]) for p_ in parts)) / len(parts)
+    eb = 2 if cfg.dtype == "bf16" else 4
+    bytes_per_launch = (eb * d + 4) * keys / launches
+    achieved = bytes_per_launch / (launch_ms * 1e-3) / 1e9
+    L_all = L * args.slabs
+    step_bytes = int(sum(STEP_BYTES(int(n), B) for n in lens)) * L_all * Hkv if eb == 2 else None
+    if args.fill and step_bytes:   # only the kept keys stored beyond the new length move
+        step_bytes = 260 * keys + 1032 * sum(p_["moved"] for p_ in parts)
+    # which of the three score kernels ran (the library's dispatch rule, restated for the label only): bf16 keys in
+    # blocks of 16 or more go to an MFMA kernel; of those, interleaved pairs to the one-key-per-lane kernel unless the
+    # cache is paged and the batch large enough for 8192-key work items
+    mfma_path = eb == 2 and (cfg.block_size == 0 or cfg.block_size >= 16)
+    waves = 8 if Hq // Hkv > 4 else 12
+    rounds = (L * S * Hkv * ((cfg.seq_len + 63) // 64)) // (4 * torch.cuda.get_device_properties(0).multi_processor_count * waves)
+    small_items = rounds * waves * 64 < 8192
+    lane = mfma_path and not args.half_split and (cfg.block_size == 0 or small_items)
+    kernel = "score_lane_kernel" if lane else "score_mfma_kernel" if mfma_path else "score_kernel"
+    roofline = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": measured_traffic(cfg.name, mode, args),
+                "launch_ms": round(launch_ms, 4), "launches_per_step": launches,
+                "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+    if step_bytes:
+        roofline["step_gbs"] = round(step_bytes / (ms * 1e-3) / 1e9, 1)
+        roofline["step_frac"] = round(step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+
+    cpu = m["cpu"]
+
+    out = {"metric": "cached keys scored+selected+compacted per second", "value": round(value, 3), "unit": "Gkeys/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": cfg.name, "positions": mode, "layers": L_all, "slabs": args.slabs, "seqs": S, "kv_heads": Hkv,
+                      "q_heads": Hq, "head_dim": d, "keys_per_seq": cfg.seq_len, "budget": B,
+                      "n_offsets": len(cfg.offsets), "storage": cfg.dtype, "layout": "paged16" if paged else "contiguous",
+                      "keys": keys, "entry": "split" if args.split else "tri_compress_step",
+                      "compaction": "fill" if args.fill else "ordered",
+                      "keys_stored": "post-rope" if args.post_rope else "pre-rope", "score_variant": args.variant, "pairs": "half-split" if args.half_split else "interleaved",
+                      "timed": "each step alone, cache restored before it" if in_place else "all steps in one bracket",
+                      "resident": bool(args.resident), "kernel_sources_sha16": kernel_sources_sha16(),
+                      "generate_s": round(t_gen, 1)},
+           "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(out), flush=True)
+
+
+def measure(args, cfg, mode, L, layer0):
+    """Generates layers layer0 .. layer0 + L - 1 of the workload on the device, runs the warm-up and the timed steps on
+    them and returns what the output line is made of; everything it allocated is released on return."""
+    import numpy as np
+    import torch
+    from paper_2604_04921_amd import binding as T
+    from workload import device, recipe
+
     dev = "cuda"
     t_gen = time.time()
-    w = device.generate(cfg, positions=mode, layers=L)
+    w = device.generate(cfg, positions=mode, layers=L, layer0=layer0)
     S, Hq, Hkv, B, d = cfg.n_seqs, cfg.n_q_heads, cfg.n_kv_heads, cfg.budget, cfg.head_dim
     model = T.Model(L, Hq, Hkv, d, cfg.rope_theta, cfg.offsets, pairs=int(args.half_split), score_variant=args.variant)
     k_view, v_view = w["k"], w["v"]
@@ -191,55 +261,13 @@ def main():
     del keep
 
     lens = w["seq_len"].cpu().numpy().astype(np.int64)
-    keys = int(lens.sum()) * L * Hkv
-    ms = elapsed * 1e3 / args.steps
-    value = keys / (ms * 1e-3) / 1e9
     k_ms = [events[2 * i].elapsed_time(events[2 * i + 1]) for i in range(launches * args.steps)]
-    launch_ms = float(np.mean(k_ms))
-    eb = 2 if cfg.dtype == "bf16" else 4
-    bytes_per_launch = (eb * d + 4) * keys / launches
-    achieved = bytes_per_launch / (launch_ms * 1e-3) / 1e9
-    step_bytes = int(sum(STEP_BYTES(int(n), B) for n in lens)) * L * Hkv if eb == 2 else None
-    if args.fill and step_bytes:   # only the kept keys stored beyond the new length move
-        moved = int((kept_idx >= kept_cnt[..., None]).sum())
-        step_bytes = 260 * keys + 1032 * moved
-    # which of the three score kernels ran (the library's dispatch rule, restated for the label only): bf16 keys in
-    # blocks of 16 or more go to an MFMA kernel; of those, interleaved pairs to the one-key-per-lane kernel unless the
-    # cache is paged and the batch large enough for 8192-key work items
-    mfma_path = eb == 2 and (cfg.block_size == 0 or cfg.block_size >= 16)
-    waves = 8 if Hq // Hkv > 4 else 12
-    rounds = (L * S * Hkv * ((cfg.seq_len + 63) // 64)) // (4 * torch.cuda.get_device_properties(0).multi_processor_count * waves)
-    small_items = rounds * waves * 64 < 8192
-    lane = mfma_path and not args.half_split and (cfg.block_size == 0 or small_items)
-    kernel = "score_lane_kernel" if lane else "score_mfma_kernel" if mfma_path else "score_kernel"
-    roofline = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(cfg.name, mode, args),
-                "launch_ms": round(launch_ms, 4), "launches_per_step": launches,
-                "algorithmic_bytes_per_launch": int(bytes_per_launch)}
-    if step_bytes:
-        roofline["step_gbs"] = round(step_bytes / (ms * 1e-3) / 1e9, 1)
-        roofline["step_frac"] = round(step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-
+    moved = int((kept_idx >= kept_cnt[..., None]).sum()) if args.fill else 0
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(cfg, cpu_sample, centers, kept_idx, kept_cnt, args.variant, args.post_rope, int(args.half_split))
-
-    out = {"metric": "cached keys scored+selected+compacted per second", "value": round(value, 3), "unit": "Gkeys/s",
-           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-           "data": "synthetic",
-           "config": {"workload": cfg.name, "positions": mode, "layers": L, "seqs": S, "kv_heads": Hkv,
-                      "q_heads": Hq, "head_dim": d, "keys_per_seq": cfg.seq_len, "budget": B,
-                      "n_offsets": len(cfg.offsets), "storage": cfg.dtype, "layout": "paged16" if paged else "contiguous",
-                      "keys": keys, "entry": "split" if args.split else "tri_compress_step",
-                      "compaction": "fill" if args.fill else "ordered",
-                      "keys_stored": "post-rope" if args.post_rope else "pre-rope", "score_variant": args.variant, "pairs": "half-split" if args.half_split else "interleaved",
-                      "timed": "each step alone, cache restored before it" if in_place else "all steps in one bracket",
-                      "resident": bool(args.resident), "kernel_sources_sha16": kernel_sources_sha16(),
-                      "generate_s": round(t_gen, 1)},
-           "roofline": roofline, "cpu_baseline": cpu}
-    print(json.dumps(out), flush=True)
+    return {"elapsed": elapsed, "keys": int(lens.sum()) * L * Hkv, "k_ms": k_ms, "launches": launches, "lens": lens,
+            "moved": moved, "cpu": cpu, "paged": paged, "in_place": in_place, "t_gen": t_gen}
 
 
 def measured_traffic(name, mode, args):
