@@ -472,11 +472,15 @@ static tri_status run_step(const tri_model *model, const float *centers, const t
     MomentLayout moments{1, 1};
     if ((rc = launch_score(*model, centers, *src, nullptr, nullptr, ws, wl, &moments, (hipStream_t)stream)) != TRI_OK)
         return rc;
+    // evicting in place with the fewest moves, the selection's workgroups do the moves themselves where they can
+    const FillTail fill{new_seq_len};
+    bool filled = false;
     if ((rc = launch_select(*model, nullptr, reinterpret_cast<const float *>(ws + wl.raw), nullptr,
                             reinterpret_cast<const double *>(ws + wl.partials), moments,
                             reinterpret_cast<uint32_t *>(ws + wl.final_), *src, budget, kept_idx, kept_cnt,
-                            (hipStream_t)stream)) != TRI_OK)
+                            (hipStream_t)stream, dst ? nullptr : &fill, &filled)) != TRI_OK)
         return rc;
+    if (filled) return TRI_OK;
     if (!dst) return tri_compact_fill(model, src, budget, kept_idx, kept_cnt, new_seq_len, stream);
     return tri_compact(model, src, dst, budget, kept_idx, kept_cnt, new_seq_len, stream);
 }

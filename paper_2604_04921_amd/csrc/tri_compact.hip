@@ -1,6 +1,6 @@
 // Eviction as compaction (Section 4.3, "evict the rest"): slot j <- slot kept_idx[j] for K, V
 // and the key positions.  Pure byte moves, 16 bytes per lane.
-#include "tri_internal.h"
+#include "tri_fill.h"
 
 namespace tri {
 
@@ -37,26 +37,11 @@ __device__ __forceinline__ int read_slot(const CompactArgs &a, const int32_t *id
     return min(max(idx[j], 0), a.src.max_seq_len - 1);
 }
 
-typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
-
-// the compacted cache is not read again by this step: non-temporal stores (the gather runs 10 % faster with them)
-__device__ __forceinline__ void store_stream16(char *p, const uint4 &v)
-{
-    __builtin_nontemporal_store(uint4v{v.x, v.y, v.z, v.w}, reinterpret_cast<uint4v *>(p));
-}
-
 // 128 threads, one pass over 8 bf16 rows: small workgroups keep the most independent row fetches in flight
 // (measured on 9.4 M scattered rows: 64 threads 1.64 ms, 128: 1.63, 256: 1.71, 512: 1.68, 1024: 1.72)
 constexpr int kGatherThreads = 128;
 constexpr int kRowsPerBlock = kGatherThreads / 16;
 
-
-// the evicted cache is read once: non-temporal hint (a streaming read is 13 % faster with it on this GPU)
-__device__ __forceinline__ uint4 load_stream16(const char *p)
-{
-    const uint4v t = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(p));
-    return make_uint4(t.x, t.y, t.z, t.w);
-}
 
 // dst and src are different memory: a plain gather.  grid (instances * ceil(B / rows per block)), block 128: the
 // row block is the fastest part of the index, so workgroups that run together write neighbouring rows.
@@ -146,93 +131,16 @@ __global__ __launch_bounds__(kInplaceThreads) void inplace_kernel(CompactArgs a)
     }
 }
 
-constexpr int kFillThreads = 256;
-constexpr int kFillMaxWords = 2048;   // budget <= 65536
-
-// In-place eviction that moves as few slots as possible (Section 4.3 fixes no slot order): kept keys already in
-// slots [0, cnt) stay; the i-th free slot below cnt (ascending) receives the i-th kept key stored at or beyond
-// cnt (ascending).  Sources (>= cnt) and destinations (< cnt) are disjoint, so the moves need no ordering.
-// grid (instances), block 256, dynamic LDS 8 * budget bytes (the move list).
+// tri_compact_fill: grid (instances), block 256, dynamic LDS 8 * budget bytes (the move list); see fill_block.
 __global__ __launch_bounds__(kFillThreads) void fill_kernel(CompactArgs a)
 {
     extern __shared__ int32_t moves[];   // [2][budget]: destination slots, source slots
     __shared__ uint32_t kept_bits[kFillMaxWords];
     __shared__ uint32_t wave_tot[kFillThreads / 64];
     __shared__ int32_t n_tail;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int inst = blockIdx.x;
-    int l, s, h;
-    decode_inst(a.src, inst, l, s, h);
-    const int cnt = read_cnt(a, inst);
-    write_new_len(a, l, s, h, cnt);
-    const int32_t *idx = a.kept_idx + (int64_t)inst * a.budget;
-    const int n_words = (cnt + 31) >> 5;
-    for (int w = tid; w < n_words; w += kFillThreads) kept_bits[w] = 0u;
-    if (tid == 0) n_tail = 0;
-    __syncthreads();
-    int my_tail = 0;
-    for (int j = tid; j < cnt; j += kFillThreads) {
-        const int n = read_slot(a, idx, j);
-        if (n < cnt) atomicOr(&kept_bits[n >> 5], 1u << (n & 31));
-        else ++my_tail;
-    }
-    if (my_tail) atomicAdd(&n_tail, my_tail);
-    __syncthreads();
-    const int first_tail = cnt - n_tail;   // idx is ascending: its last n_tail entries lie at or beyond cnt
-    // free slots below cnt, in ascending order, paired with the tail survivors
-    int done = 0;
-    for (int w0 = 0; w0 < n_words; w0 += kFillThreads) {
-        const int w = w0 + tid;
-        uint32_t free_bits = 0u;
-        if (w < n_words) {
-            free_bits = ~kept_bits[w];
-            if (w == n_words - 1 && (cnt & 31)) free_bits &= (1u << (cnt & 31)) - 1u;
-        }
-        const uint32_t c = (uint32_t)__popc(free_bits);
-        uint32_t cum = c;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t t = __shfl_up(cum, o, 64);
-            if (lane >= o) cum += t;
-        }
-        if (lane == 63) wave_tot[wave] = cum;
-        __syncthreads();
-        uint32_t before = cum - c, total = 0u;
-        for (int k = 0; k < kFillThreads / 64; ++k) {
-            if (k < wave) before += wave_tot[k];
-            total += wave_tot[k];
-        }
-        int o = done + (int)before;
-        while (free_bits) {
-            const int bit = __ffs(free_bits) - 1;
-            free_bits &= free_bits - 1u;
-            if (o < n_tail) {   // always true for an ascending duplicate-free kept_idx; guards the reads otherwise
-                moves[o] = (w << 5) + bit;
-                moves[a.budget + o] = read_slot(a, idx, first_tail + o);
-            }
-            ++o;
-        }
-        done = min(done + (int)total, n_tail);
-        __syncthreads();
-    }
-    // done == n_tail moves; 16 bytes of K and of V per thread and move
-    const int rows_per_pass = kFillThreads / a.row16;
-    const int r = tid / a.row16, part = tid % a.row16;
-    char *kb = (char *)a.dst.k, *vb = (char *)a.dst.v;
-    int32_t *pb = const_cast<int32_t *>(a.dst.pos);
-    for (int m0 = 0; m0 < done; m0 += rows_per_pass) {
-        const int m = m0 + r;
-        if (m >= done) continue;
-        const int dj = moves[m], sn = moves[a.budget + m];
-        const int64_t so = kv_offset(a.src, l, s, h, sn) * a.elem_bytes + part * 16;
-        const int64_t d_o = kv_offset(a.dst, l, s, h, dj) * a.elem_bytes + part * 16;
-        const uint4 kv = load_stream16(kb + so);
-        const uint4 vv = load_stream16(vb + so);
-        store_stream16(kb + d_o, kv);
-        store_stream16(vb + d_o, vv);
-        if (part == 0) pb[pos_offset(a.dst, l, s, h, dj)] = pb[pos_offset(a.src, l, s, h, sn)];
-    }
+    const FillArgs f{a.src, a.new_seq_len, a.budget, a.elem_bytes, a.row16};
+    fill_block(f, inst, read_cnt(a, inst), a.kept_idx + (int64_t)inst * a.budget, moves, kept_bits, wave_tot, &n_tail);
 }
 
 }  // namespace

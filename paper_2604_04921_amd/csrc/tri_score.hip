@@ -360,30 +360,6 @@ tri_status launch_score_kernel(const tri_model &m, const ScoreArgs &sa, dim3 gri
     return hip_status("score_kernel");
 }
 
-// Compute units of the current GPU (asked once per GPU).
-tri_status device_cus(int *n_cu)
-{
-    constexpr int kDevices = 64;
-    static std::atomic<int> cached[kDevices];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kDevices) {
-        (void)hipGetLastError();
-        set_error("score: no current device below %d", kDevices);
-        return TRI_ERR_HIP;
-    }
-    int n = cached[dev].load(std::memory_order_relaxed);
-    if (n == 0) {
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
-            (void)hipGetLastError();
-            set_error("score: compute-unit count not available");
-            return TRI_ERR_HIP;
-        }
-        cached[dev].store(n, std::memory_order_relaxed);
-    }
-    *n_cu = n;
-    return TRI_OK;
-}
-
 // MFMA kernel: bf16, a group of 16 slots never straddling a block, 32-bit row offsets
 bool mfma_path(const tri_cache &c, int G)
 {
@@ -441,6 +417,30 @@ tri_status launch_score_g(const tri_model &m, const tri_cache &c, ScoreArgs sa, 
 }
 
 }  // namespace
+
+// Compute units of the current GPU (asked once per GPU).
+tri_status device_cus(int *n_cu)
+{
+    constexpr int kDevices = 64;
+    static std::atomic<int> cached[kDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kDevices) {
+        (void)hipGetLastError();
+        set_error("score: no current device below %d", kDevices);
+        return TRI_ERR_HIP;
+    }
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            set_error("score: compute-unit count not available");
+            return TRI_ERR_HIP;
+        }
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    *n_cu = n;
+    return TRI_OK;
+}
 
 tri_status launch_score(const tri_model &m, const float *centers, const tri_cache &c, float *final_out,
                         float *raw_out, char *ws, const Workspace &wl, MomentLayout *moments, hipStream_t st)

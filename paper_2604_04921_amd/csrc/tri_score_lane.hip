@@ -33,7 +33,6 @@ namespace {
 constexpr int kMaxDevices = 64;
 
 typedef float float4v __attribute__((ext_vector_type(4)));
-typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int kTileKeys = 64;
 constexpr int kStageBytes = kTileKeys * 128;                    // one half row per key, swizzled, no padding
@@ -45,12 +44,6 @@ constexpr int lane_wave_bytes(int G) { return kStageBytes + 2 * lane_heads(G) * 
 constexpr int lane_lds_bytes(int G, bool rotated)
 {
     return (rotated ? 0 : kLanePhasorBytes) + lane_heads(G) * kTabRow * 4 + lane_waves(G) * lane_wave_bytes(G);
-}
-
-__device__ __forceinline__ uint4 load_stream16(const char *p)
-{
-    const uint4v t = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(p));
-    return make_uint4(t.x, t.y, t.z, t.w);
 }
 
 // Byte offset of (key k, 16-byte piece p of its half row) in a wave's staging area.  Rows k and k ^ 1 swap places when

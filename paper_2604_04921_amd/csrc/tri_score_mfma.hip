@@ -106,15 +106,7 @@ struct LaneTable {
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
-
-// 16-byte streaming load: K rows are read exactly once, so they are fetched with the non-temporal hint
-// (measured on this GPU: a streaming read reaches 7.0 TB/s with it and 6.2 TB/s without).
-__device__ __forceinline__ uint4 load_stream16(const char *p)
-{
-    const uint4v t = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(p));
-    return make_uint4(t.x, t.y, t.z, t.w);
-}
+// (K rows are read exactly once: load_stream16, the 16-byte load with the non-temporal hint.)
 
 // ROTATE = false: the key is stored post-RoPE, already k e^{i w p}.
 // HALF = false: kd holds the (re, im) pairs of the lane's four bands; HALF = true (half-split layout):

@@ -8,7 +8,7 @@
 // integer keys in registers (select_reg_kernel: one histogram over linear score bins, exact ranking of
 // the threshold bin); longer ones use select_kernel (the same steps over keys held in LDS or, beyond
 // 32768 keys, in a workspace area).
-#include "tri_internal.h"
+#include "tri_fill.h"
 
 namespace tri {
 
@@ -40,6 +40,9 @@ struct SelectArgs {
     int32_t n_seqs, n_kv_heads, max_seq_len, budget, lds_keys;
     const int32_t *head_budgets;   // [L][Hkv] or NULL: budget of each (layer, KV head), at most `budget`
     int32_t n_above, n_upto;       // select_kernel: this launch handles the head-instances with n_above < N <= n_upto
+    // 256-thread select_reg_kernel, fill != 0: the workgroup goes on to evict its head-instance in place (fill_block)
+    FillArgs fa;
+    int32_t fill;
 };
 
 // The budget of head-instance `inst`: the common one, or the head's own (read into [0, budget]).
@@ -291,8 +294,9 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
     constexpr int kWaves = THREADS / 64;
     constexpr int kBinsPerThread = kSelBins / THREADS;
     __shared__ uint32_t hist[kSelBins];
-    __shared__ uint32_t cand_key[kSelCand];
-    __shared__ int32_t cand_idx[kSelCand];
+    __shared__ uint32_t cand_store[2 * kSelCand];   // candidate keys, then their slots (later the fill's move list)
+    uint32_t *const cand_key = cand_store;
+    int32_t *const cand_idx = reinterpret_cast<int32_t *>(cand_store + kSelCand);
     __shared__ uint32_t row_g[KPT * kWaves], row_e[KPT * kWaves];   // [row j][wave], then exclusive prefixes
     __shared__ uint32_t scan_tot[2][kWaves];
     __shared__ uint32_t sh[36];   // 0: selected bin, 1: need inside it, 2: candidate count, 3: threshold key, 4..35: bit counters / tie count
@@ -305,9 +309,23 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
     const int B = instance_budget(a, inst);
     int32_t *out = a.kept_idx + (int64_t)inst * a.budget;
     if (tid == 0) a.kept_cnt[inst] = N < B ? N : B;
-    if (B == 0) return;   // a head whose own budget is 0 keeps nothing
+    // the eviction in place that may follow: the histogram and the candidate arrays are free by then
+    auto fill_tail = [&](int cnt) {
+        if constexpr (THREADS == kFillThreads) {
+            if (a.fill) {
+                __syncthreads();   // out[] is complete and nobody reads hist or the candidates any more
+                fill_block(a.fa, inst, cnt, out, reinterpret_cast<int32_t *>(cand_store), hist, scan_tot[0],
+                           reinterpret_cast<int32_t *>(&sh[0]));
+            }
+        }
+    };
+    if (B == 0) {   // a head whose own budget is 0 keeps nothing
+        fill_tail(0);
+        return;
+    }
     if (N <= B) {  // nothing to evict: keep every slot
         for (int n = tid; n < N; n += THREADS) out[n] = n;
+        fill_tail(N);
         return;
     }
     for (int k = tid; k < kSelBins; k += THREADS) hist[k] = 0u;
@@ -514,6 +532,7 @@ __global__ __launch_bounds__(THREADS) void select_reg_kernel(SelectArgs a)
         const uint32_t e_before = row_e[j * kWaves + wave] + (uint32_t)__popcll(em & below);
         if (gt || (eq && e_before < need)) out[g_before + (e_before < need ? e_before : need)] = n;
     }
+    fill_tail(B);
 }
 
 template <int G>
@@ -556,14 +575,33 @@ tri_status launch_select_g(const SelectArgs &sa, int n_inst, hipStream_t st)
 
 tri_status launch_select(const tri_model &m, const float *final_scores, const float *raw, const double *stats,
                          const double *partials, MomentLayout moments, uint32_t *scratch, const tri_cache &c,
-                         int32_t budget, int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st)
+                         int32_t budget, int32_t *kept_idx, int32_t *kept_cnt, hipStream_t st, const FillTail *fill,
+                         bool *fill_taken)
 {
+    if (fill_taken) *fill_taken = false;
     const int n_inst = m.n_layers * c.n_seqs * m.n_kv_heads;
     if (n_inst <= 0) return TRI_OK;
     SelectArgs sa{final_scores, raw, stats, partials, moments.n_tiles, moments.tile_keys, scratch, c.seq_len, kept_idx,
                   kept_cnt, c.n_seqs, m.n_kv_heads,
                   c.max_seq_len, budget, c.max_seq_len < kSelLdsKeys ? (c.max_seq_len > 0 ? c.max_seq_len : 1) : kSelLdsKeys,
                   m.head_budgets, -1, c.max_seq_len};
+    sa.fill = 0;
+    // Sequences short enough for the 256-thread kernel, whose workgroup is the fill's: the eviction in place rides
+    // along (its move list takes the candidate arrays' place, so the budget may not exceed their length) -- on small
+    // batches, whose workgroups are all resident at once (eight per CU): there the launch saved counts (one sequence
+    // of 288 head-instances: 0.147 -> 0.142 ms per step, four: 0.299 -> 0.291), whereas 18432 head-instances take
+    // 0.74 ms this way against 0.21 + 0.44 ms as two launches.
+    int n_cu = 0;
+    if (fill && fill_taken && c.max_seq_len <= 16 * kFillThreads && budget <= kSelCand) {
+        const tri_status rcu = device_cus(&n_cu);
+        if (rcu != TRI_OK) return rcu;
+    }
+    if (n_cu > 0 && n_inst <= 8 * n_cu) {
+        sa.fa = FillArgs{make_view(m, c), fill->new_seq_len, budget, c.dtype == TRI_BF16 ? 2 : 4,
+                         kHeadDim * (c.dtype == TRI_BF16 ? 2 : 4) / 16};
+        sa.fill = 1;
+        *fill_taken = true;
+    }
     if (final_scores) return launch_select_g<0>(sa, n_inst, st);
     switch (m.n_q_heads / m.n_kv_heads) {
         case 1: return launch_select_g<1>(sa, n_inst, st);

@@ -105,3 +105,73 @@ def test_fill_large_budget(oracle):
                         budget=9001, n_calib=128)
     run_fill(oracle, cfg, "suffix")
     run_fill(oracle, cfg, "random")
+
+
+def fused_fill_against_the_three_calls(cfg, paged=False, head_budgets=None, mutate=None):
+    """tri_compress_step with dst = NULL (eviction in place, fewest moves) against tri_score + tri_select_topk +
+    tri_compact_fill on a second copy of the same cache: kept slots, counts, new lengths and every byte of K, V and
+    the positions must agree (the selection on final scores and the one inside the fused step share their z-score,
+    so the kept sets are the same bits)."""
+    w = recipe.generate(cfg)
+    if mutate is not None:
+        mutate(w)
+    a = GpuRun(cfg, w, paged=paged, head_budgets=head_budgets)
+    b = GpuRun(cfg, w, paged=paged, head_budgets=head_budgets)
+    a.build_centers()
+    b.centers.copy_(a.centers)
+    a.score()
+    a.select()
+    a.B.tri_compact_fill(a.model, a.cache, cfg.budget, a.kept_idx, a.kept_cnt, a.new_len)
+    b.B.tri_compress_step(b.model, b.centers, b.cache, None, cfg.budget, b.kept_idx, b.kept_cnt, b.new_len, b.ws)
+    torch.cuda.synchronize()
+    cnt = a.kept_cnt.cpu().numpy()
+    np.testing.assert_array_equal(b.kept_cnt.cpu().numpy(), cnt)
+    np.testing.assert_array_equal(b.new_len.cpu().numpy(), a.new_len.cpu().numpy())
+    ia, ib = a.kept_idx.cpu().numpy(), b.kept_idx.cpu().numpy()
+    for l in range(cfg.n_layers):
+        for s in range(cfg.n_seqs):
+            for h in range(cfg.n_kv_heads):
+                c = int(cnt[l, s, h])
+                np.testing.assert_array_equal(ib[l, s, h, :c], ia[l, s, h, :c])
+    for name in ("k", "v"):
+        np.testing.assert_array_equal(to_numpy(getattr(b, name)), to_numpy(getattr(a, name)), err_msg=name)
+    np.testing.assert_array_equal(b.pos.cpu().numpy(), a.pos.cpu().numpy())
+    return cnt
+
+
+def test_fused_fill_ragged_lengths():
+    """Lengths below, at and above the budget, an empty sequence, one of a single key: the selection's workgroups do
+    the eviction themselves (sequences of at most 4096 keys, budget at most 2048)."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=2, n_seqs=8, n_q_heads=8, n_kv_heads=2, seq_len=3000,
+                        min_seq_len=3000, budget=300, n_calib=128)
+
+    def lens(w):
+        w["seq_len"][:] = np.array([3000, 0, 1, 299, 300, 301, 428, 2999], dtype=np.int32)
+    cnt = fused_fill_against_the_three_calls(cfg, mutate=lens)
+    assert cnt[0, :, 0].tolist() == [300, 0, 1, 299, 300, 300, 300, 300]
+
+
+def test_fused_fill_head_budgets():
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=2, n_seqs=3, n_q_heads=8, n_kv_heads=2, seq_len=900,
+                        min_seq_len=200, budget=300, n_calib=128)
+    fused_fill_against_the_three_calls(cfg, head_budgets=np.array([[300, 37], [0, 5000]], dtype=np.int32))
+
+
+def test_fused_fill_paged():
+    cfg = recipe.scaled(recipe.CONFIGS["c4_paged"], n_layers=2, n_seqs=3, n_q_heads=8, n_kv_heads=2, seq_len=900,
+                        min_seq_len=100, budget=160, n_calib=128)
+    fused_fill_against_the_three_calls(cfg, paged=True)
+
+
+def test_fused_fill_fp32():
+    cfg = recipe.scaled(recipe.CONFIGS["c1_tiny"], n_layers=1, n_seqs=2, seq_len=300, budget=64)
+    fused_fill_against_the_three_calls(cfg)
+
+
+@pytest.mark.parametrize("seq_len,budget", [(4096, 2048), (4097, 2048), (4096, 2049), (9000, 700)])
+def test_fused_fill_at_the_limits_of_the_short_kernel(seq_len, budget):
+    """4096 keys and a budget of 2048 are the most the selection's own eviction takes; one more of either and the step
+    launches tri_compact_fill's kernel after the selection, as it does for longer sequences."""
+    cfg = recipe.scaled(recipe.CONFIGS["c2_layer"], n_layers=1, n_seqs=2, n_q_heads=8, n_kv_heads=2, seq_len=seq_len,
+                        min_seq_len=seq_len, budget=budget, n_calib=128)
+    fused_fill_against_the_three_calls(cfg)
