@@ -329,6 +329,11 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
                 }
                 // memory instructions may move across; vector and matrix instructions stay apart
                 __builtin_amdgcn_sched_barrier(0x4 | 0x20 | 0x100);
+                // A wave in its vector part outranks the waves that are in their matrix runs (whose instructions each
+                // hold the pipe for eight cycles and leave issue slots between them): measured in one process, 36 x 16 x 8
+                // head-instances of 32768 keys 7.90 -> 7.60 ms, sparse positions 8.51 -> 8.01, G = 8 (64 x 8 of 131072 keys)
+                // 4.63 -> 4.38; the other way round gains half of that, the levels themselves (1 / 0, 3 / 0, 2 / 1) nothing.
+                __builtin_amdgcn_s_setprio(0);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
 #pragma unroll
@@ -347,6 +352,7 @@ __global__ __launch_bounds__(lane_waves(G) * 64) void score_lane_kernel(ScoreArg
                         acc[q] = __builtin_amdgcn_mfma_f32_4x4x1f32(m[k], t_[k], acc[q], 0, 0, 0);
                     }
                 }
+                __builtin_amdgcn_s_setprio(2);
                 __builtin_amdgcn_sched_barrier(0x4 | 0x20 | 0x100);
             };
             auto score_tile = [&](auto table_tag, auto mirror_tag) {
