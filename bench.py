@@ -59,7 +59,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="score variant (0 full, 1 trig only, 2 norm only, 3 un-weighted norm)")
     ap.add_argument("--resident", action="store_true",
                     help="measurement aid: every head-instance reads the K rows of the first one (strides 0), so the "
-                         "score kernel runs out of the caches instead of HBM; not the benchmark")
+                         "score kernel reads 8 MB over and over instead of streaming from HBM (out of the last-level "
+                         "cache rather than L2, since work items take their tiles in rotated orders); not the benchmark")
     ap.add_argument("--inst-probe", action="store_true",
                     help="instead of the benchmark, print the issue rates of the instructions the score kernel is made of")
     ap.add_argument("--copy-calibration", action="store_true",
